@@ -1,0 +1,183 @@
+/* hh.h -- C ABI of the per-GPU pipeline-stage step of a Llama-style model.
+ *
+ * Scope.  In hybrid-parallel training each accelerator owns a pipeline stage of
+ * 1..k consecutive transformer layers and processes the batch as micro-batches
+ * (paper Section 2.3); its run time is the forward and backward pass of those
+ * layers.  This library is that per-device work for Llama2 decoder layers (the
+ * model family of Section 4.2 / Table 1) on one gfx950 GPU: hand-written HIP
+ * kernels only.  The per-layer timings it exports are the "computation
+ * performance of the operator or layer" that the performance predictor of
+ * Section 3.2 samples from each accelerator type.
+ *
+ * Layer (pre-norm Llama decoder layer, no bias, no dropout), T = micro_batch*seq
+ * tokens, H hidden, A = n_heads*head_dim, F = ffn:
+ *     xn = rmsnorm(x; g_attn)          q,k,v = xn Wq^T, xn Wk^T, xn Wv^T
+ *     q,k <- rope(q), rope(k)          (pairs (i, i+head_dim/2), angle pos*base^(-2i/d))
+ *     a  = causal_softmax(q k^T / sqrt(d)) v      per (sample, head)
+ *     h  = x + a Wo^T                  hn = rmsnorm(h; g_mlp)
+ *     y  = h + (silu(hn Wg^T) * (hn Wu^T)) Wd^T
+ * rmsnorm(t; g) = t * g / sqrt(mean(t^2) + rms_eps).  When the shapes are one
+ * tensor-parallel share (A != H), a Wo^T and m Wd^T are that share's partial
+ * sums and are added to the residual as they are: the all-reduce between
+ * shares is not part of this library.
+ *
+ * General rules
+ *  - Every function returns HH_OK (0) or a negative hh_status; none aborts,
+ *    throws or prints.  hh_last_error() gives a message for the calling thread.
+ *  - All tensor pointers are DEVICE pointers unless a parameter says "host".
+ *    The caller owns every buffer; the hot calls (hh_layer_fwd, hh_layer_bwd,
+ *    hh_stage_step) allocate nothing except, once per context, the rotary
+ *    cos/sin table for a new (seq, head_dim, rope_base); hh_ctx_reserve does
+ *    that ahead of time.
+ *  - The hot calls enqueue work on `stream` (a hipStream_t passed as void*,
+ *    NULL = the null stream) and return without synchronising.
+ *  - Layouts: activations [micro_batch, seq, feat] row-major contiguous;
+ *    weights [out, in] row-major.  dtype HH_BF16: activations and weights are
+ *    bfloat16, accumulation fp32, parameter gradients fp32.  dtype HH_F32:
+ *    everything fp32.
+ *  - Every pointer must be 16-byte aligned (HH_ERR_MISALIGNED otherwise).
+ *  - Shapes: head_dim 64 or 128; n_kv_heads == n_heads; hidden, n_heads*head_dim
+ *    and ffn multiples of 64 for HH_BF16 and multiples of 8 for HH_F32; any
+ *    seq >= 1, micro_batch >= 1; each tensor below 2^31 elements
+ *    (HH_ERR_UNSUPPORTED_SHAPE otherwise).
+ *  - Argument validation happens before any GPU work is enqueued.
+ */
+#ifndef HH_H
+#define HH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HH_OK = 0,
+    HH_ERR_INVALID_ARG = -1,       /* null pointer, non-positive count, bad enum */
+    HH_ERR_UNSUPPORTED_SHAPE = -2, /* see "Shapes" above */
+    HH_ERR_BUFFER_TOO_SMALL = -3,
+    HH_ERR_MISALIGNED = -4,
+    HH_ERR_DEVICE = -5             /* a HIP runtime call failed; text in hh_last_error() */
+} hh_status;
+
+typedef enum { HH_F32 = 0, HH_BF16 = 1 } hh_dtype;
+
+/* Shape of one decoder layer and of the micro-batch it processes. */
+typedef struct {
+    int32_t hidden;       /* H */
+    int32_t n_heads;      /* heads held by this GPU */
+    int32_t n_kv_heads;   /* must equal n_heads */
+    int32_t head_dim;     /* d: 64 or 128 */
+    int32_t ffn;          /* F: SwiGLU width held by this GPU */
+    int32_t seq;          /* S */
+    int32_t micro_batch;  /* B: samples per micro-batch */
+    float rms_eps;        /* inside the square root, added to the mean of squares */
+    float rope_base;
+    int32_t dtype;        /* hh_dtype */
+} hh_layer_cfg;
+
+/* Parameters of one layer, in the storage dtype.  wq, wk, wv may be three rows
+ * blocks of one [3A, H] allocation, w_gate and w_up of one [2F, H] allocation:
+ * the library then runs one GEMM instead of three / two. */
+typedef struct {
+    const void *g_attn;  /* [H]    */
+    const void *wq;      /* [A, H] */
+    const void *wk;      /* [A, H] */
+    const void *wv;      /* [A, H] */
+    const void *wo;      /* [H, A] */
+    const void *g_mlp;   /* [H]    */
+    const void *w_gate;  /* [F, H] */
+    const void *w_up;    /* [F, H] */
+    const void *w_down;  /* [H, F] */
+} hh_layer_weights;
+
+/* Parameter gradients, always fp32, same shapes as the weights. */
+typedef struct {
+    float *g_attn, *wq, *wk, *wv, *wo, *g_mlp, *w_gate, *w_up, *w_down;
+} hh_layer_grads;
+
+/* One node of the predictor's weighted graph (Section 3.2): measured time of one
+ * layer on this device plus the memory figures the workload simulator needs. */
+typedef struct {
+    int32_t layer;
+    float fwd_ms, bwd_ms;          /* median over the timed iterations */
+    double fwd_flop, bwd_flop;     /* model flops: GEMM 2mnk, causal attention 4*d per (query, key<=query) pair */
+    float fwd_tflops, bwd_tflops;
+    uint64_t weight_bytes;         /* parameters in the storage dtype */
+    uint64_t grad_bytes;           /* fp32 parameter gradients */
+    uint64_t saved_act_bytes;      /* activations kept from forward to backward, per micro-batch */
+    uint64_t p2p_bytes;            /* stage-boundary message, Eq. (3): micro_batch*seq*hidden*2 */
+} hh_profile_rec;
+
+typedef struct hh_ctx hh_ctx;      /* opaque: device id, rotary table */
+
+/* Thread-local description of the last error on this thread ("" if none). */
+const char *hh_last_error(void);
+
+/* Create / destroy a context on HIP device `device`.  HH_ERR_DEVICE when there
+ * is no such GPU.  Destroy frees the rotary table; it does not synchronise. */
+int hh_ctx_create(hh_ctx **out, int device);
+int hh_ctx_destroy(hh_ctx *ctx);
+/* Build the rotary table for cfg now (allocates, copies, synchronises). */
+int hh_ctx_reserve(hh_ctx *ctx, const hh_layer_cfg *cfg);
+
+/* Model flops of one layer on one micro-batch (host arithmetic only). */
+int hh_layer_flops(const hh_layer_cfg *cfg, double *fwd_flop, double *bwd_flop);
+
+/* Bytes of the `saved` block of one layer x micro-batch and of the scratch
+ * `workspace` that one fwd or bwd call needs (contents of workspace need not
+ * survive between calls).  Host arithmetic only; validates cfg. */
+int hh_layer_sizes(const hh_layer_cfg *cfg, size_t *saved_bytes, size_t *workspace_bytes);
+
+/* Forward of one layer.  x [B,S,H] in, y [B,S,H] out (y must not alias x).
+ * `saved` (>= saved_bytes) receives what backward needs besides x itself:
+ * xn, rotated q and k, v, a, h, hn, gate, up, the softmax log-sum-exp and both
+ * inverse RMS vectors.  saved == NULL runs forward only; workspace must then
+ * hold saved_bytes + workspace_bytes. */
+int hh_layer_fwd(hh_ctx *ctx, const hh_layer_cfg *cfg, const hh_layer_weights *w,
+                 const void *x, void *y, void *saved, void *workspace, void *stream);
+
+/* Backward of one layer.  x and saved as given to / written by hh_layer_fwd;
+ * dy [B,S,H] in; dx [B,S,H] out (dx may alias dy).  accumulate == 0 writes the
+ * nine gradients, != 0 adds to them (fp32). */
+int hh_layer_bwd(hh_ctx *ctx, const hh_layer_cfg *cfg, const hh_layer_weights *w,
+                 const void *x, const void *saved, const void *dy, void *dx,
+                 const hh_layer_grads *grads, int accumulate, void *workspace, void *stream);
+
+/* Sizes for a stage of n_layers layers over n_micro micro-batches: the pool
+ * keeps every layer's saved block and the activations between layers for all
+ * micro-batches (forward of all micro-batches precedes backward). */
+int hh_stage_sizes(const hh_layer_cfg *cfg, int n_layers, int n_micro,
+                   size_t *saved_pool_bytes, size_t *workspace_bytes);
+
+/* One pipeline-stage step (Section 2.3): for m in 0..n_micro-1 run x[m] through
+ * layers 0..n_layers-1 into y[m]; then for m in 0..n_micro-1 run dy[m] back
+ * through layers n_layers-1..0 into dx[m], summing parameter gradients over
+ * micro-batches in fp32 (plain sum).  x, y, dy, dx are HOST arrays of n_micro
+ * device pointers; w and g are HOST arrays of n_layers structs.
+ * zero_grads_first != 0: the first micro-batch overwrites the gradients,
+ * otherwise the step adds to what the buffers hold.  No allocation, no
+ * synchronisation, no host-device copies. */
+int hh_stage_step(hh_ctx *ctx, const hh_layer_cfg *cfg, int n_layers, const hh_layer_weights *w,
+                  int n_micro, const void *const *x, void *const *y,
+                  const void *const *dy, void *const *dx,
+                  const hh_layer_grads *g, int zero_grads_first,
+                  void *saved_pool, void *workspace, void *stream);
+
+/* Time every layer of a stage (Sections 1 and 3.2: automatic profiling that
+ * feeds the predictor).  Runs the stage on x / dy (device, [B,S,H]) with
+ * `warmup` untimed and `iters` timed repetitions, bracketing each layer's
+ * forward and backward with HIP events, and fills out[0..n_layers-1] (HOST).
+ * Gradients are accumulated into g (values are meaningless afterwards).
+ * saved_pool / workspace sized by hh_stage_sizes(cfg, n_layers, 1).
+ * Synchronises the stream. */
+int hh_layer_profile(hh_ctx *ctx, const hh_layer_cfg *cfg, int n_layers, const hh_layer_weights *w,
+                     const hh_layer_grads *g, const void *x, const void *dy,
+                     int warmup, int iters, void *saved_pool, void *workspace,
+                     hh_profile_rec *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HH_H */

@@ -1,0 +1,181 @@
+"""ctypes binding of libhh.so: the same entry points as include/hh.h, argument marshalling only.
+
+Every numeric step runs in the library's HIP kernels.  PyTorch tensors are used
+as owners of device memory (``tensor.data_ptr()``) and for the current stream;
+there is no fallback path: if the library is missing, importing fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Sequence
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhh.so")
+
+HH_OK = 0
+HH_ERR_INVALID_ARG = -1
+HH_ERR_UNSUPPORTED_SHAPE = -2
+HH_ERR_BUFFER_TOO_SMALL = -3
+HH_ERR_MISALIGNED = -4
+HH_ERR_DEVICE = -5
+HH_F32 = 0
+HH_BF16 = 1
+
+WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
+EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
+           "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_layer_profile")
+
+
+class hh_layer_cfg(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("seq", C.c_int32), ("micro_batch", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_base", C.c_float), ("dtype", C.c_int32)]
+
+
+class hh_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class hh_layer_grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class hh_profile_rec(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("fwd_ms", C.c_float), ("bwd_ms", C.c_float), ("fwd_flop", C.c_double),
+                ("bwd_flop", C.c_double), ("fwd_tflops", C.c_float), ("bwd_tflops", C.c_float),
+                ("weight_bytes", C.c_uint64), ("grad_bytes", C.c_uint64), ("saved_act_bytes", C.c_uint64),
+                ("p2p_bytes", C.c_uint64)]
+
+
+class HHError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("hh error %d: %s" % (code, msg))
+        self.code = code
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("%s is missing: build it with `python -m paper_2405_16256_amd.build` "
+                          "(there is no fallback path)" % _LIB_PATH)
+    lib = C.CDLL(_LIB_PATH)
+    vp, i, sz = C.c_void_p, C.c_int, C.POINTER(C.c_size_t)
+    cfgp, wp, gp = C.POINTER(hh_layer_cfg), C.POINTER(hh_layer_weights), C.POINTER(hh_layer_grads)
+    lib.hh_last_error.restype = C.c_char_p
+    lib.hh_last_error.argtypes = []
+    sigs = {
+        "hh_ctx_create": [C.POINTER(vp), i],
+        "hh_ctx_destroy": [vp],
+        "hh_ctx_reserve": [vp, cfgp],
+        "hh_layer_flops": [cfgp, C.POINTER(C.c_double), C.POINTER(C.c_double)],
+        "hh_layer_sizes": [cfgp, sz, sz],
+        "hh_layer_fwd": [vp, cfgp, wp, vp, vp, vp, vp, vp],
+        "hh_layer_bwd": [vp, cfgp, wp, vp, vp, vp, vp, gp, i, vp, vp],
+        "hh_stage_sizes": [cfgp, i, i, sz, sz],
+        "hh_stage_step": [vp, cfgp, i, wp, i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), gp, i, vp, vp, vp],
+        "hh_layer_profile": [vp, cfgp, i, wp, gp, vp, vp, i, i, vp, vp, C.POINTER(hh_profile_rec), vp],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = args
+    return lib
+
+
+lib = _load()
+
+
+def hh_last_error() -> str:
+    return lib.hh_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != HH_OK:
+        raise HHError(rc, hh_last_error())
+
+
+def _ptr(t) -> int | None:
+    """Device address of a torch tensor, or an int / None passed through."""
+    if t is None or isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def make_cfg(hidden, n_heads, head_dim, ffn, seq, micro_batch=1, rms_eps=1e-5, rope_base=10000.0, dtype=HH_BF16,
+             n_kv_heads=None) -> hh_layer_cfg:
+    return hh_layer_cfg(hidden, n_heads, n_heads if n_kv_heads is None else n_kv_heads, head_dim, ffn, seq,
+                        micro_batch, rms_eps, rope_base, dtype)
+
+
+def make_weights(w: dict) -> hh_layer_weights:
+    return hh_layer_weights(*[_ptr(w[n]) for n in WEIGHT_FIELDS])
+
+
+def make_grads(g: dict) -> hh_layer_grads:
+    return hh_layer_grads(*[_ptr(g[n]) for n in WEIGHT_FIELDS])
+
+
+def hh_ctx_create(device: int = 0) -> int:
+    out = C.c_void_p()
+    _check(lib.hh_ctx_create(C.byref(out), device))
+    return out.value
+
+
+def hh_ctx_destroy(ctx: int) -> None:
+    _check(lib.hh_ctx_destroy(ctx))
+
+
+def hh_ctx_reserve(ctx: int, cfg: hh_layer_cfg) -> None:
+    _check(lib.hh_ctx_reserve(ctx, C.byref(cfg)))
+
+
+def hh_layer_flops(cfg: hh_layer_cfg) -> tuple[float, float]:
+    f, b = C.c_double(), C.c_double()
+    _check(lib.hh_layer_flops(C.byref(cfg), C.byref(f), C.byref(b)))
+    return f.value, b.value
+
+
+def hh_layer_sizes(cfg: hh_layer_cfg) -> tuple[int, int]:
+    s, w = C.c_size_t(), C.c_size_t()
+    _check(lib.hh_layer_sizes(C.byref(cfg), C.byref(s), C.byref(w)))
+    return s.value, w.value
+
+
+def hh_stage_sizes(cfg: hh_layer_cfg, n_layers: int, n_micro: int) -> tuple[int, int]:
+    s, w = C.c_size_t(), C.c_size_t()
+    _check(lib.hh_stage_sizes(C.byref(cfg), n_layers, n_micro, C.byref(s), C.byref(w)))
+    return s.value, w.value
+
+
+def hh_layer_fwd(ctx, cfg, weights: hh_layer_weights, x, y, saved, workspace, stream=0) -> None:
+    _check(lib.hh_layer_fwd(ctx, C.byref(cfg), C.byref(weights), _ptr(x), _ptr(y), _ptr(saved), _ptr(workspace), stream))
+
+
+def hh_layer_bwd(ctx, cfg, weights: hh_layer_weights, x, saved, dy, dx, grads: hh_layer_grads, accumulate, workspace,
+                 stream=0) -> None:
+    _check(lib.hh_layer_bwd(ctx, C.byref(cfg), C.byref(weights), _ptr(x), _ptr(saved), _ptr(dy), _ptr(dx),
+                            C.byref(grads), int(accumulate), _ptr(workspace), stream))
+
+
+def _ptr_array(ts: Sequence):
+    return (C.c_void_p * len(ts))(*[_ptr(t) for t in ts])
+
+
+def hh_stage_step(ctx, cfg, weights: Sequence[hh_layer_weights], x: Sequence, y: Sequence, dy: Sequence, dx: Sequence,
+                  grads: Sequence[hh_layer_grads], zero_grads_first, saved_pool, workspace, stream=0) -> None:
+    k, m = len(weights), len(x)
+    assert len(grads) == k and len(y) == m and len(dy) == m and len(dx) == m
+    warr = (hh_layer_weights * k)(*weights)
+    garr = (hh_layer_grads * k)(*grads)
+    _check(lib.hh_stage_step(ctx, C.byref(cfg), k, warr, m, _ptr_array(x), _ptr_array(y), _ptr_array(dy), _ptr_array(dx),
+                             garr, int(zero_grads_first), _ptr(saved_pool), _ptr(workspace), stream))
+
+
+def hh_layer_profile(ctx, cfg, weights: Sequence[hh_layer_weights], grads: Sequence[hh_layer_grads], x, dy, warmup, iters,
+                     saved_pool, workspace, stream=0) -> list[hh_profile_rec]:
+    k = len(weights)
+    warr = (hh_layer_weights * k)(*weights)
+    garr = (hh_layer_grads * k)(*grads)
+    out = (hh_profile_rec * k)()
+    _check(lib.hh_layer_profile(ctx, C.byref(cfg), k, warr, garr, _ptr(x), _ptr(dy), warmup, iters, _ptr(saved_pool),
+                                _ptr(workspace), out, stream))
+    return list(out)

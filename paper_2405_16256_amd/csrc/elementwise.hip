@@ -1,0 +1,263 @@
+// HBM-bound kernels of the decoder layer: RMSNorm forward/backward (with the
+// residual gradient folded in), rotary embedding, SwiGLU forward/backward and
+// the column-sum reduction for the gain gradients.  All global accesses are
+// 16-byte vectors along the contiguous feature dimension; math is fp32.
+#include "common.h"
+#include "kernels.h"
+
+namespace hh {
+
+constexpr int TPB = 256;
+constexpr int NWAVES = TPB / WAVE;
+
+// ------------------------------------------------------------------ RMSNorm
+template <typename T>
+__global__ __launch_bounds__(TPB) void k_rmsnorm_fwd(const T* __restrict__ x, const T* __restrict__ g,
+                                                     T* __restrict__ xn, float* __restrict__ r, int H, float eps) {
+    constexpr int V = Vec<T>::N;
+    __shared__ float red[NWAVES];
+    const size_t base = (size_t)blockIdx.x * H;
+    float ss = 0.f;
+    for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+        float f[V];
+        Vec<T>::load(x + base + c, f);
+#pragma unroll
+        for (int e = 0; e < V; e++) ss += f[e] * f[e];
+    }
+    ss = block_sum<NWAVES>(ss, red);
+    const float rs = 1.0f / sqrtf(ss / (float)H + eps);
+    if (threadIdx.x == 0) r[blockIdx.x] = rs;
+    for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+        float f[V], gg[V];
+        Vec<T>::load(x + base + c, f);
+        Vec<T>::load(g + c, gg);
+#pragma unroll
+        for (int e = 0; e < V; e++) f[e] = f[e] * rs * gg[e];
+        Vec<T>::store(xn + base + c, f);
+    }
+}
+
+// One workgroup walks `rpb` consecutive rows.  Column j is always handled by the
+// same thread, so the per-column sums of dxn*u live in LDS without atomics.
+template <typename T>
+__global__ __launch_bounds__(TPB) void k_rmsnorm_bwd(const T* __restrict__ dxn, const T* __restrict__ x,
+                                                     const float* __restrict__ r, const T* __restrict__ g,
+                                                     const T* __restrict__ dres, T* __restrict__ dx,
+                                                     float* __restrict__ partial, int T_rows, int H, int rpb) {
+    constexpr int V = Vec<T>::N;
+    extern __shared__ float colacc[];  // [H]
+    __shared__ float red[NWAVES];
+    for (int c = threadIdx.x * V; c < H; c += TPB * V)
+#pragma unroll
+        for (int e = 0; e < V; e++) colacc[c + e] = 0.f;
+    const int row0 = blockIdx.x * rpb;
+    const int row1 = min(T_rows, row0 + rpb);
+    const float invH = 1.0f / (float)H;
+    for (int row = row0; row < row1; row++) {
+        const size_t base = (size_t)row * H;
+        const float rs = r[row];
+        float s = 0.f;
+        for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+            float d[V], xx[V], gg[V];
+            Vec<T>::load(dxn + base + c, d);
+            Vec<T>::load(x + base + c, xx);
+            Vec<T>::load(g + c, gg);
+#pragma unroll
+            for (int e = 0; e < V; e++) s += d[e] * gg[e] * xx[e];
+        }
+        const float c1 = block_sum<NWAVES>(s, red) * rs * invH;  // mean_j(w_j u_j)
+        for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+            float d[V], xx[V], gg[V], rr[V], o[V];
+            Vec<T>::load(dxn + base + c, d);
+            Vec<T>::load(x + base + c, xx);
+            Vec<T>::load(g + c, gg);
+            Vec<T>::load(dres + base + c, rr);
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                const float u = xx[e] * rs;
+                colacc[c + e] += d[e] * u;
+                o[e] = rr[e] + rs * (d[e] * gg[e] - u * c1);
+            }
+            Vec<T>::store(dx + base + c, o);
+        }
+    }
+    float* out = partial + (size_t)blockIdx.x * H;
+    for (int c = threadIdx.x * V; c < H; c += TPB * V)
+#pragma unroll
+        for (int e = 0; e < V; e++) out[c + e] = colacc[c + e];
+}
+
+// out[j] (=|+=) sum_b partial[b][j].  64 columns x 4 row groups per workgroup.
+__global__ __launch_bounds__(TPB) void k_colsum_reduce(const float* __restrict__ partial, int nblk, int H,
+                                                       float* __restrict__ out, int accumulate) {
+    __shared__ float red[NWAVES][WAVE];
+    const int cx = threadIdx.x % WAVE, ry = threadIdx.x / WAVE;
+    const int col = blockIdx.x * WAVE + cx;
+    float s = 0.f;
+    if (col < H)
+        for (int b = ry; b < nblk; b += NWAVES) s += partial[(size_t)b * H + col];
+    red[ry][cx] = s;
+    __syncthreads();
+    if (ry == 0 && col < H) {
+        float t = red[0][cx] + red[1][cx] + red[2][cx] + red[3][cx];
+        out[col] = accumulate ? out[col] + t : t;
+    }
+}
+
+// --------------------------------------------------------------------- RoPE
+// One thread rotates V pairs (i, i + d/2) of one head of one token, for q or k.
+template <typename T>
+__global__ __launch_bounds__(TPB) void k_rope(T* __restrict__ qkv, int ld, int Ttok, int S, int nh, int d,
+                                              const float* __restrict__ table, float sin_sign) {
+    constexpr int V = Vec<T>::N;
+    const int half = d / 2;
+    const int vph = half / V;               // vectors per head-half
+    const long total = (long)Ttok * 2 * nh * vph;
+    const long idx = (long)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= total) return;
+    const int iv = (int)(idx % vph);
+    long rest = idx / vph;
+    const int head = (int)(rest % nh); rest /= nh;
+    const int which = (int)(rest % 2);
+    const int t = (int)(rest / 2);
+    const int pos = t % S;
+    T* p = qkv + (size_t)t * ld + (size_t)which * nh * d + head * d + iv * V;
+    const float* cs = table + ((size_t)pos * half + iv * V);
+    const float* sn = cs + (size_t)S * half;
+    float a[V], b[V], oa[V], ob[V];
+    Vec<T>::load(p, a);
+    Vec<T>::load(p + half, b);
+#pragma unroll
+    for (int e = 0; e < V; e++) {
+        const float c = cs[e], s = sin_sign * sn[e];
+        oa[e] = a[e] * c - b[e] * s;
+        ob[e] = b[e] * c + a[e] * s;
+    }
+    Vec<T>::store(p, oa);
+    Vec<T>::store(p + half, ob);
+}
+
+// ------------------------------------------------------------------- SwiGLU
+template <typename T>
+__global__ __launch_bounds__(TPB) void k_swiglu_fwd(const T* __restrict__ gu, T* __restrict__ m, int Ttok, int F) {
+    constexpr int V = Vec<T>::N;
+    const int vpr = F / V;
+    const long idx = (long)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= (long)Ttok * vpr) return;
+    const int t = (int)(idx / vpr), c = (int)(idx % vpr) * V;
+    float gt[V], u[V], o[V];
+    Vec<T>::load(gu + (size_t)t * 2 * F + c, gt);
+    Vec<T>::load(gu + (size_t)t * 2 * F + F + c, u);
+#pragma unroll
+    for (int e = 0; e < V; e++) o[e] = gt[e] / (1.0f + expf(-gt[e])) * u[e];
+    Vec<T>::store(m + (size_t)t * F + c, o);
+}
+
+template <typename T>
+__global__ __launch_bounds__(TPB) void k_swiglu_bwd(const T* __restrict__ dm, const T* __restrict__ gu,
+                                                    T* __restrict__ dgu, T* __restrict__ m, int Ttok, int F) {
+    constexpr int V = Vec<T>::N;
+    const int vpr = F / V;
+    const long idx = (long)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= (long)Ttok * vpr) return;
+    const int t = (int)(idx / vpr), c = (int)(idx % vpr) * V;
+    float gt[V], u[V], d[V], og[V], ou[V], om[V];
+    Vec<T>::load(gu + (size_t)t * 2 * F + c, gt);
+    Vec<T>::load(gu + (size_t)t * 2 * F + F + c, u);
+    Vec<T>::load(dm + (size_t)t * F + c, d);
+#pragma unroll
+    for (int e = 0; e < V; e++) {
+        const float sg = 1.0f / (1.0f + expf(-gt[e]));
+        const float sl = gt[e] * sg;
+        om[e] = sl * u[e];
+        og[e] = d[e] * u[e] * sg * (1.0f + gt[e] * (1.0f - sg));
+        ou[e] = d[e] * sl;
+    }
+    Vec<T>::store(dgu + (size_t)t * 2 * F + c, og);
+    Vec<T>::store(dgu + (size_t)t * 2 * F + F + c, ou);
+    Vec<T>::store(m + (size_t)t * F + c, om);
+}
+
+// ---------------------------------------------------------------- launchers
+static inline unsigned nblocks(long n) { return (unsigned)((n + TPB - 1) / TPB); }
+
+hipError_t rmsnorm_fwd(int dtype, const void* x, const void* g, void* xn, float* r, int T, int H, float eps,
+                       hipStream_t st) {
+    if (dtype == DT_BF16)
+        k_rmsnorm_fwd<bf16_t><<<T, TPB, 0, st>>>((const bf16_t*)x, (const bf16_t*)g, (bf16_t*)xn, r, H, eps);
+    else
+        k_rmsnorm_fwd<float><<<T, TPB, 0, st>>>((const float*)x, (const float*)g, (float*)xn, r, H, eps);
+    return hipGetLastError();
+}
+
+static inline int rms_rows_per_block(int T) {
+    int rpb = 8;
+    while ((T + rpb - 1) / rpb > 512) rpb *= 2;
+    return rpb;
+}
+int rmsnorm_bwd_blocks(int T) {
+    const int rpb = rms_rows_per_block(T);
+    return (T + rpb - 1) / rpb;
+}
+
+hipError_t rmsnorm_bwd(int dtype, const void* dxn, const void* x, const float* r, const void* g, const void* dres,
+                       void* dx, float* partial, int T, int H, hipStream_t st) {
+    const int rpb = rms_rows_per_block(T);
+    const int nblk = (T + rpb - 1) / rpb;
+    const size_t lds = (size_t)H * sizeof(float);
+    hipError_t e;
+    if (dtype == DT_BF16) {
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute((const void*)k_rmsnorm_bwd<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        k_rmsnorm_bwd<bf16_t><<<nblk, TPB, lds, st>>>((const bf16_t*)dxn, (const bf16_t*)x, r, (const bf16_t*)g,
+                                                      (const bf16_t*)dres, (bf16_t*)dx, partial, T, H, rpb);
+    } else {
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute((const void*)k_rmsnorm_bwd<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        k_rmsnorm_bwd<float><<<nblk, TPB, lds, st>>>((const float*)dxn, (const float*)x, r, (const float*)g,
+                                                     (const float*)dres, (float*)dx, partial, T, H, rpb);
+    }
+    return hipGetLastError();
+}
+
+hipError_t colsum_reduce(const float* partial, int nblk, int H, float* out, int accumulate, hipStream_t st) {
+    k_colsum_reduce<<<(H + WAVE - 1) / WAVE, TPB, 0, st>>>(partial, nblk, H, out, accumulate);
+    return hipGetLastError();
+}
+
+hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nh, int d, const float* table, int backward,
+                hipStream_t st) {
+    const float sgn = backward ? -1.0f : 1.0f;
+    if (dtype == DT_BF16) {
+        const long n = (long)T * 2 * nh * (d / 2 / Vec<bf16_t>::N);
+        k_rope<bf16_t><<<nblocks(n), TPB, 0, st>>>((bf16_t*)qkv, ld, T, S, nh, d, table, sgn);
+    } else {
+        const long n = (long)T * 2 * nh * (d / 2 / Vec<float>::N);
+        k_rope<float><<<nblocks(n), TPB, 0, st>>>((float*)qkv, ld, T, S, nh, d, table, sgn);
+    }
+    return hipGetLastError();
+}
+
+hipError_t swiglu_fwd(int dtype, const void* gu, void* m, int T, int F, hipStream_t st) {
+    if (dtype == DT_BF16)
+        k_swiglu_fwd<bf16_t><<<nblocks((long)T * (F / 8)), TPB, 0, st>>>((const bf16_t*)gu, (bf16_t*)m, T, F);
+    else
+        k_swiglu_fwd<float><<<nblocks((long)T * (F / 4)), TPB, 0, st>>>((const float*)gu, (float*)m, T, F);
+    return hipGetLastError();
+}
+
+hipError_t swiglu_bwd(int dtype, const void* dm, const void* gu, void* dgu, void* m, int T, int F, hipStream_t st) {
+    if (dtype == DT_BF16)
+        k_swiglu_bwd<bf16_t><<<nblocks((long)T * (F / 8)), TPB, 0, st>>>((const bf16_t*)dm, (const bf16_t*)gu,
+                                                                          (bf16_t*)dgu, (bf16_t*)m, T, F);
+    else
+        k_swiglu_bwd<float><<<nblocks((long)T * (F / 4)), TPB, 0, st>>>((const float*)dm, (const float*)gu,
+                                                                         (float*)dgu, (float*)m, T, F);
+    return hipGetLastError();
+}
+
+}  // namespace hh

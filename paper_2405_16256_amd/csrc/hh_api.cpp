@@ -1,0 +1,552 @@
+// C ABI of the decoder-stage library: argument validation, buffer carving and
+// the order in which the gfx950 kernels are enqueued.  No numeric work happens
+// on the host except the rotary cos/sin table (built once per context).
+#include "../../include/hh.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+namespace hh {
+hipError_t gemm_bf16(const GemmDesc& g, hipStream_t st);
+hipError_t gemm_f32(const GemmDesc& g, hipStream_t st);
+hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st);
+hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
+                         void* dqkv, int B, int S, int nh, int d, hipStream_t st);
+hipError_t attn_f32_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st);
+hipError_t attn_f32_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
+                        void* dqkv, int B, int S, int nh, int d, hipStream_t st);
+
+hipError_t gemm(int dtype, const GemmDesc& g, hipStream_t st) {
+    return dtype == DT_BF16 ? gemm_bf16(g, st) : gemm_f32(g, st);
+}
+hipError_t attn_fwd(int dtype, const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_bf16_fwd(qkv, ld, o, lse, B, S, nh, d, st) : attn_f32_fwd(qkv, ld, o, lse, B, S, nh, d, st);
+}
+hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
+                    void* dqkv, int B, int S, int nh, int d, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, d, st)
+                            : attn_f32_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, d, st);
+}
+}  // namespace hh
+
+using namespace hh;
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+static int hip_fail(hipError_t e, const char* what) {
+    return fail(HH_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+#define HIP_TRY(call)                                        \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);    \
+    } while (0)
+
+extern "C" const char* hh_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------ context
+struct hh_ctx {
+    int device;
+    float* rope_table;  // device: cos[S][d/2] then sin[S][d/2]
+    int rope_seq, rope_dim;
+    float rope_base;
+};
+
+extern "C" int hh_ctx_create(hh_ctx** out, int device) {
+    if (!out) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out is NULL");
+    *out = nullptr;
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDeviceCount");
+    if (device < 0 || device >= n) return fail(HH_ERR_DEVICE, "hh_ctx_create: no HIP device %d (%d visible)", device, n);
+    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f};
+    if (!c) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out of host memory");
+    *out = c;
+    return HH_OK;
+}
+
+extern "C" int hh_ctx_destroy(hh_ctx* ctx) {
+    if (!ctx) return HH_OK;
+    if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+    delete ctx;
+    return HH_OK;
+}
+
+// ---------------------------------------------------------------- validation
+static int check_cfg(const hh_layer_cfg* c) {
+    if (!c) return fail(HH_ERR_INVALID_ARG, "cfg is NULL");
+    if (c->dtype != HH_F32 && c->dtype != HH_BF16) return fail(HH_ERR_INVALID_ARG, "cfg.dtype %d is not HH_F32/HH_BF16", c->dtype);
+    if (c->hidden <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->ffn <= 0 || c->seq <= 0 || c->micro_batch <= 0)
+        return fail(HH_ERR_INVALID_ARG, "cfg has a non-positive dimension");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(HH_ERR_INVALID_ARG, "cfg.rms_eps must be >= 0 and rope_base > 0");
+    if (c->n_kv_heads != c->n_heads)
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "n_kv_heads (%d) must equal n_heads (%d)", c->n_kv_heads, c->n_heads);
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(HH_ERR_UNSUPPORTED_SHAPE, "head_dim %d: only 64 and 128", c->head_dim);
+    const int mult = c->dtype == HH_BF16 ? 64 : 8;
+    const long A = (long)c->n_heads * c->head_dim;
+    if (c->hidden % mult || A % mult || c->ffn % mult)
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "hidden, n_heads*head_dim and ffn must be multiples of %d for this dtype", mult);
+    if (c->hidden > 32768) return fail(HH_ERR_UNSUPPORTED_SHAPE, "hidden %d exceeds 32768", c->hidden);
+    const long T = (long)c->seq * c->micro_batch;
+    const long lim = (1L << 31) - (1L << 25);
+    const long wide = std::max<long>(std::max<long>(c->hidden, 3 * A), 2L * c->ffn);
+    if (wide > 65535) return fail(HH_ERR_UNSUPPORTED_SHAPE, "a row of %ld elements exceeds 65535", wide);
+    if (T * wide >= lim || (long)c->hidden * std::max<long>(3 * A, 2L * c->ffn) >= lim)
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "a tensor would reach 2^31 elements");
+    return HH_OK;
+}
+
+static int check_ptr(const void* p, const char* name) {
+    if (!p) return fail(HH_ERR_INVALID_ARG, "%s is NULL", name);
+    if ((uintptr_t)p & 15) return fail(HH_ERR_MISALIGNED, "%s is not 16-byte aligned", name);
+    return HH_OK;
+}
+#define TRY(x)                \
+    do {                      \
+        int rc_ = (x);        \
+        if (rc_ != HH_OK) return rc_; \
+    } while (0)
+
+static int check_weights(const hh_layer_weights* w) {
+    if (!w) return fail(HH_ERR_INVALID_ARG, "weights is NULL");
+    TRY(check_ptr(w->g_attn, "weights.g_attn")); TRY(check_ptr(w->wq, "weights.wq")); TRY(check_ptr(w->wk, "weights.wk"));
+    TRY(check_ptr(w->wv, "weights.wv")); TRY(check_ptr(w->wo, "weights.wo")); TRY(check_ptr(w->g_mlp, "weights.g_mlp"));
+    TRY(check_ptr(w->w_gate, "weights.w_gate")); TRY(check_ptr(w->w_up, "weights.w_up")); TRY(check_ptr(w->w_down, "weights.w_down"));
+    return HH_OK;
+}
+static int check_grads(const hh_layer_grads* g) {
+    if (!g) return fail(HH_ERR_INVALID_ARG, "grads is NULL");
+    TRY(check_ptr(g->g_attn, "grads.g_attn")); TRY(check_ptr(g->wq, "grads.wq")); TRY(check_ptr(g->wk, "grads.wk"));
+    TRY(check_ptr(g->wv, "grads.wv")); TRY(check_ptr(g->wo, "grads.wo")); TRY(check_ptr(g->g_mlp, "grads.g_mlp"));
+    TRY(check_ptr(g->w_gate, "grads.w_gate")); TRY(check_ptr(g->w_up, "grads.w_up")); TRY(check_ptr(g->w_down, "grads.w_down"));
+    return HH_OK;
+}
+
+// ------------------------------------------------------------ buffer layouts
+static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Dims {
+    int T, H, A, F, S, B, nh, d, dt;
+    size_t es;
+};
+static Dims dims_of(const hh_layer_cfg* c) {
+    Dims d;
+    d.S = c->seq; d.B = c->micro_batch; d.T = c->seq * c->micro_batch; d.H = c->hidden; d.nh = c->n_heads; d.d = c->head_dim;
+    d.A = c->n_heads * c->head_dim; d.F = c->ffn; d.dt = c->dtype == HH_BF16 ? DT_BF16 : DT_F32; d.es = dt_size(d.dt);
+    return d;
+}
+
+struct SavedLayout {
+    size_t xn, qkv, a, h, hn, gu, lse, r1, r2, total;
+};
+static SavedLayout saved_layout(const Dims& d) {
+    SavedLayout s;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+    const size_t T = d.T;
+    s.xn = take(T * d.H * d.es);
+    s.qkv = take(T * 3 * d.A * d.es);
+    s.a = take(T * d.A * d.es);
+    s.h = take(T * d.H * d.es);
+    s.hn = take(T * d.H * d.es);
+    s.gu = take(T * 2 * d.F * d.es);
+    s.lse = take((size_t)d.B * d.nh * d.S * 4);
+    s.r1 = take(T * 4);
+    s.r2 = take(T * 4);
+    s.total = off;
+    return s;
+}
+
+struct WorkLayout {
+    size_t m, dgu, dhn, dh, da, dqkv, dvec, partial, total;
+};
+static WorkLayout work_layout(const Dims& d) {
+    WorkLayout w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
+    const size_t T = d.T;
+    w.m = take(T * d.F * d.es);            // forward: m; backward: dm, then m recomputed in place
+    w.dgu = take(T * 2 * d.F * d.es);
+    w.dhn = take(T * d.H * d.es);          // d(hn), later d(xn)
+    w.dh = take(T * d.H * d.es);
+    w.da = take(T * d.A * d.es);
+    w.dqkv = take(T * 3 * d.A * d.es);
+    w.dvec = take((size_t)d.B * d.nh * d.S * 4);
+    w.partial = take((size_t)rmsnorm_bwd_blocks(d.T) * d.H * 4);
+    w.total = off;
+    return w;
+}
+
+extern "C" int hh_layer_sizes(const hh_layer_cfg* cfg, size_t* saved_bytes, size_t* workspace_bytes) {
+    TRY(check_cfg(cfg));
+    const Dims d = dims_of(cfg);
+    if (saved_bytes) *saved_bytes = saved_layout(d).total;
+    if (workspace_bytes) *workspace_bytes = work_layout(d).total;
+    return HH_OK;
+}
+
+static size_t act_bytes(const Dims& d) { return up256((size_t)d.T * d.H * d.es); }
+
+extern "C" int hh_stage_sizes(const hh_layer_cfg* cfg, int n_layers, int n_micro, size_t* saved_pool_bytes,
+                              size_t* workspace_bytes) {
+    TRY(check_cfg(cfg));
+    if (n_layers <= 0 || n_micro <= 0) return fail(HH_ERR_INVALID_ARG, "n_layers and n_micro must be positive");
+    const Dims d = dims_of(cfg);
+    const size_t per_micro = (size_t)n_layers * saved_layout(d).total + (size_t)(n_layers - 1) * act_bytes(d);
+    if (saved_pool_bytes) *saved_pool_bytes = per_micro * (size_t)n_micro;
+    if (workspace_bytes) *workspace_bytes = work_layout(d).total + act_bytes(d);  // + the gradient passed between layers
+    return HH_OK;
+}
+
+extern "C" int hh_layer_flops(const hh_layer_cfg* cfg, double* fwd_flop, double* bwd_flop) {
+    TRY(check_cfg(cfg));
+    const Dims d = dims_of(cfg);
+    const double T = d.T;
+    const double gemm = T * (8.0 * d.A * d.H + 6.0 * (double)d.H * d.F);
+    const double attn = 4.0 * d.d * d.B * d.nh * ((double)d.S * (d.S + 1) / 2);
+    if (fwd_flop) *fwd_flop = gemm + attn;
+    if (bwd_flop) *bwd_flop = 2.0 * (gemm + attn);
+    return HH_OK;
+}
+
+// ------------------------------------------------------------- rotary table
+static int ensure_rope(hh_ctx* ctx, const hh_layer_cfg* c) {
+    if (ctx->rope_table && ctx->rope_seq >= c->seq && ctx->rope_dim == c->head_dim && ctx->rope_base == c->rope_base) return HH_OK;
+    HIP_TRY(hipSetDevice(ctx->device));
+    if (ctx->rope_table) {
+        HIP_TRY(hipDeviceSynchronize());  // earlier launches may still read the old table
+        HIP_TRY(hipFree(ctx->rope_table));
+        ctx->rope_table = nullptr;
+    }
+    const int S = c->seq, half = c->head_dim / 2;
+    std::vector<float> host((size_t)2 * S * half);
+    for (int i = 0; i < half; i++) {
+        const double theta = std::pow((double)c->rope_base, -2.0 * i / c->head_dim);
+        for (int s = 0; s < S; s++) {
+            const double phi = s * theta;
+            host[(size_t)s * half + i] = (float)std::cos(phi);
+            host[(size_t)S * half + (size_t)s * half + i] = (float)std::sin(phi);
+        }
+    }
+    HIP_TRY(hipMalloc((void**)&ctx->rope_table, host.size() * sizeof(float)));
+    HIP_TRY(hipMemcpy(ctx->rope_table, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice));
+    ctx->rope_seq = S; ctx->rope_dim = c->head_dim; ctx->rope_base = c->rope_base;
+    return HH_OK;
+}
+
+extern "C" int hh_ctx_reserve(hh_ctx* ctx, const hh_layer_cfg* cfg) {
+    TRY(check_cfg(cfg));
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    return ensure_rope(ctx, cfg);
+}
+
+// ------------------------------------------------------------ layer forward
+static inline char* at(void* base, size_t off) { return (char*)base + off; }
+static inline const char* at(const void* base, size_t off) { return (const char*)base + off; }
+
+static GemmDesc desc(int kind, int M, int N, int K, const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+                     const void* R = nullptr, int ldr = 0, int out_f32 = 0, int acc = 0) {
+    GemmDesc g;
+    g.kind = kind; g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+    g.R = R; g.ldr = ldr; g.out_f32 = out_f32; g.accumulate = acc;
+    return g;
+}
+
+static int layer_fwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, const hh_layer_weights* w, const void* x,
+                          void* y, void* saved, void* ws, hipStream_t st) {
+    const SavedLayout sl = saved_layout(d);
+    const WorkLayout wl = work_layout(d);
+    const int T = d.T, H = d.H, A = d.A, F = d.F, dt = d.dt;
+    const size_t es = d.es;
+    void* xn = at(saved, sl.xn); void* qkv = at(saved, sl.qkv); void* a = at(saved, sl.a); void* h = at(saved, sl.h);
+    void* hn = at(saved, sl.hn); void* gu = at(saved, sl.gu);
+    float* lse = (float*)at(saved, sl.lse); float* r1 = (float*)at(saved, sl.r1); float* r2 = (float*)at(saved, sl.r2);
+    void* m = at(ws, wl.m);
+
+    HIP_TRY(rmsnorm_fwd(dt, x, w->g_attn, xn, r1, T, H, cfg->rms_eps, st));
+    const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
+                            (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
+    if (qkv_packed) {
+        HIP_TRY(gemm(dt, desc(GEMM_NT, T, 3 * A, H, xn, H, w->wq, H, qkv, 3 * A), st));
+    } else {
+        const void* ws3[3] = {w->wq, w->wk, w->wv};
+        for (int i = 0; i < 3; i++)
+            HIP_TRY(gemm(dt, desc(GEMM_NT, T, A, H, xn, H, ws3[i], H, at(qkv, (size_t)i * A * es), 3 * A), st));
+    }
+    HIP_TRY(rope(dt, qkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, 0, st));
+    HIP_TRY(attn_fwd(dt, qkv, 3 * A, a, lse, d.B, d.S, d.nh, d.d, st));
+    HIP_TRY(gemm(dt, desc(GEMM_NT, T, H, A, a, A, w->wo, A, h, H, x, H), st));
+    HIP_TRY(rmsnorm_fwd(dt, h, w->g_mlp, hn, r2, T, H, cfg->rms_eps, st));
+    const bool gu_packed = (const char*)w->w_up == (const char*)w->w_gate + (size_t)F * H * es;
+    if (gu_packed) {
+        HIP_TRY(gemm(dt, desc(GEMM_NT, T, 2 * F, H, hn, H, w->w_gate, H, gu, 2 * F), st));
+    } else {
+        HIP_TRY(gemm(dt, desc(GEMM_NT, T, F, H, hn, H, w->w_gate, H, gu, 2 * F), st));
+        HIP_TRY(gemm(dt, desc(GEMM_NT, T, F, H, hn, H, w->w_up, H, at(gu, (size_t)F * es), 2 * F), st));
+    }
+    HIP_TRY(swiglu_fwd(dt, gu, m, T, F, st));
+    HIP_TRY(gemm(dt, desc(GEMM_NT, T, H, F, m, F, w->w_down, F, y, H, h, H), st));
+    return HH_OK;
+}
+
+extern "C" int hh_layer_fwd(hh_ctx* ctx, const hh_layer_cfg* cfg, const hh_layer_weights* w, const void* x, void* y,
+                            void* saved, void* workspace, void* stream) {
+    TRY(check_cfg(cfg));
+    TRY(check_weights(w));
+    TRY(check_ptr(x, "x")); TRY(check_ptr(y, "y")); TRY(check_ptr(workspace, "workspace"));
+    if (saved && ((uintptr_t)saved & 15)) return fail(HH_ERR_MISALIGNED, "saved is not 16-byte aligned");
+    if (x == y) return fail(HH_ERR_INVALID_ARG, "y must not alias x");
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    TRY(ensure_rope(ctx, cfg));
+    const Dims d = dims_of(cfg);
+    void* sv = saved;
+    void* wsp = workspace;
+    if (!sv) {  // forward only: the saved block lives at the front of the workspace
+        sv = workspace;
+        wsp = at(workspace, saved_layout(d).total);
+    }
+    return layer_fwd_impl(ctx, d, cfg, w, x, y, sv, wsp, (hipStream_t)stream);
+}
+
+// ----------------------------------------------------------- layer backward
+static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, const hh_layer_weights* w, const void* x,
+                          const void* saved, const void* dy, void* dx, const hh_layer_grads* g, int acc, void* ws,
+                          hipStream_t st) {
+    (void)cfg;
+    const SavedLayout sl = saved_layout(d);
+    const WorkLayout wl = work_layout(d);
+    const int T = d.T, H = d.H, A = d.A, F = d.F, dt = d.dt;
+    const size_t es = d.es;
+    const void* xn = at(saved, sl.xn); const void* qkv = at(saved, sl.qkv); const void* a = at(saved, sl.a);
+    const void* h = at(saved, sl.h); const void* hn = at(saved, sl.hn); const void* gu = at(saved, sl.gu);
+    const float* lse = (const float*)at(saved, sl.lse);
+    const float* r1 = (const float*)at(saved, sl.r1); const float* r2 = (const float*)at(saved, sl.r2);
+    void* m = at(ws, wl.m); void* dgu = at(ws, wl.dgu); void* dhn = at(ws, wl.dhn); void* dh = at(ws, wl.dh);
+    void* da = at(ws, wl.da); void* dqkv = at(ws, wl.dqkv);
+    float* dvec = (float*)at(ws, wl.dvec); float* partial = (float*)at(ws, wl.partial);
+    const int nblk = rmsnorm_bwd_blocks(T);
+    acc = acc ? 1 : 0;
+
+    // MLP branch: y = h + m Wd^T
+    HIP_TRY(gemm(dt, desc(GEMM_NN, T, F, H, dy, H, w->w_down, F, m, F), st));                 // dm (in the m buffer)
+    HIP_TRY(swiglu_bwd(dt, m, gu, dgu, m, T, F, st));                                          // dgate|dup, m
+    HIP_TRY(gemm(dt, desc(GEMM_TN, H, F, T, dy, H, m, F, g->w_down, F, nullptr, 0, 1, acc), st));
+    const bool gu_packed = (const char*)w->w_up == (const char*)w->w_gate + (size_t)F * H * es;
+    const bool dgu_packed = (char*)g->w_up == (char*)g->w_gate + (size_t)F * H * 4;
+    if (dgu_packed) {
+        HIP_TRY(gemm(dt, desc(GEMM_TN, 2 * F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
+    } else {
+        HIP_TRY(gemm(dt, desc(GEMM_TN, F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
+        HIP_TRY(gemm(dt, desc(GEMM_TN, F, H, T, at(dgu, (size_t)F * es), 2 * F, hn, H, g->w_up, H, nullptr, 0, 1, acc), st));
+    }
+    if (gu_packed) {
+        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, 2 * F, dgu, 2 * F, w->w_gate, H, dhn, H), st));
+    } else {
+        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, F, dgu, 2 * F, w->w_gate, H, dhn, H), st));
+        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, F, at(dgu, (size_t)F * es), 2 * F, w->w_up, H, dhn, H, dhn, H), st));
+    }
+    HIP_TRY(rmsnorm_bwd(dt, dhn, h, r2, w->g_mlp, dy, dh, partial, T, H, st));                // dh = dy + norm-bwd
+    HIP_TRY(colsum_reduce(partial, nblk, H, g->g_mlp, acc, st));
+
+    // attention branch: h = x + a Wo^T
+    HIP_TRY(gemm(dt, desc(GEMM_TN, H, A, T, dh, H, a, A, g->wo, A, nullptr, 0, 1, acc), st));
+    HIP_TRY(gemm(dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
+    HIP_TRY(attn_bwd(dt, qkv, 3 * A, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.d, st));
+    HIP_TRY(rope(dt, dqkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, 1, st));
+    const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
+                            (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
+    const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)A * H * 4;
+    if (dqkv_packed) {
+        HIP_TRY(gemm(dt, desc(GEMM_TN, 3 * A, H, T, dqkv, 3 * A, xn, H, g->wq, H, nullptr, 0, 1, acc), st));
+    } else {
+        float* gs[3] = {g->wq, g->wk, g->wv};
+        for (int i = 0; i < 3; i++)
+            HIP_TRY(gemm(dt, desc(GEMM_TN, A, H, T, at(dqkv, (size_t)i * A * es), 3 * A, xn, H, gs[i], H, nullptr, 0, 1, acc), st));
+    }
+    void* dxn = dhn;
+    if (qkv_packed) {
+        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, 3 * A, dqkv, 3 * A, w->wq, H, dxn, H), st));
+    } else {
+        const void* ws3[3] = {w->wq, w->wk, w->wv};
+        for (int i = 0; i < 3; i++)
+            HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, A, at(dqkv, (size_t)i * A * es), 3 * A, ws3[i], H, dxn, H,
+                                  i ? dxn : nullptr, H), st));
+    }
+    HIP_TRY(rmsnorm_bwd(dt, dxn, x, r1, w->g_attn, dh, dx, partial, T, H, st));              // dx = dh + norm-bwd
+    HIP_TRY(colsum_reduce(partial, nblk, H, g->g_attn, acc, st));
+    return HH_OK;
+}
+
+extern "C" int hh_layer_bwd(hh_ctx* ctx, const hh_layer_cfg* cfg, const hh_layer_weights* w, const void* x,
+                            const void* saved, const void* dy, void* dx, const hh_layer_grads* grads, int accumulate,
+                            void* workspace, void* stream) {
+    TRY(check_cfg(cfg));
+    TRY(check_weights(w));
+    TRY(check_grads(grads));
+    TRY(check_ptr(x, "x")); TRY(check_ptr(saved, "saved")); TRY(check_ptr(dy, "dy")); TRY(check_ptr(dx, "dx"));
+    TRY(check_ptr(workspace, "workspace"));
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    TRY(ensure_rope(ctx, cfg));
+    const Dims d = dims_of(cfg);
+    return layer_bwd_impl(ctx, d, cfg, w, x, saved, dy, dx, grads, accumulate, workspace, (hipStream_t)stream);
+}
+
+// --------------------------------------------------------------- stage step
+struct StagePool {
+    size_t saved_sz, act_sz, per_micro;
+    char* base;
+    int k;
+    void* saved(int m, int l) const { return base + (size_t)m * per_micro + (size_t)l * (saved_sz + act_sz); }
+    // output of layer l (< k-1) = input of layer l+1
+    void* act(int m, int l) const { return base + (size_t)m * per_micro + (size_t)l * (saved_sz + act_sz) + saved_sz; }
+};
+static StagePool stage_pool(const Dims& d, int k, void* pool) {
+    StagePool p;
+    p.saved_sz = saved_layout(d).total; p.act_sz = act_bytes(d); p.k = k;
+    p.per_micro = (size_t)k * p.saved_sz + (size_t)(k - 1) * p.act_sz;
+    p.base = (char*)pool;
+    return p;
+}
+
+static int check_stage_args(const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w, const hh_layer_grads* g) {
+    TRY(check_cfg(cfg));
+    if (n_layers <= 0) return fail(HH_ERR_INVALID_ARG, "n_layers must be positive");
+    if (!w || !g) return fail(HH_ERR_INVALID_ARG, "weights / grads array is NULL");
+    for (int l = 0; l < n_layers; l++) {
+        TRY(check_weights(&w[l]));
+        TRY(check_grads(&g[l]));
+    }
+    return HH_OK;
+}
+
+extern "C" int hh_stage_step(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w, int n_micro,
+                             const void* const* x, void* const* y, const void* const* dy, void* const* dx,
+                             const hh_layer_grads* g, int zero_grads_first, void* saved_pool, void* workspace, void* stream) {
+    TRY(check_stage_args(cfg, n_layers, w, g));
+    if (n_micro <= 0) return fail(HH_ERR_INVALID_ARG, "n_micro must be positive");
+    if (!x || !y || !dy || !dx) return fail(HH_ERR_INVALID_ARG, "x / y / dy / dx pointer array is NULL");
+    for (int m = 0; m < n_micro; m++) {
+        TRY(check_ptr(x[m], "x[m]")); TRY(check_ptr(y[m], "y[m]")); TRY(check_ptr(dy[m], "dy[m]")); TRY(check_ptr(dx[m], "dx[m]"));
+        if (x[m] == y[m]) return fail(HH_ERR_INVALID_ARG, "y[m] must not alias x[m]");
+    }
+    TRY(check_ptr(saved_pool, "saved_pool")); TRY(check_ptr(workspace, "workspace"));
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    TRY(ensure_rope(ctx, cfg));
+    const Dims d = dims_of(cfg);
+    const StagePool p = stage_pool(d, n_layers, saved_pool);
+    hipStream_t st = (hipStream_t)stream;
+    for (int m = 0; m < n_micro; m++)
+        for (int l = 0; l < n_layers; l++) {
+            const void* in = l == 0 ? x[m] : p.act(m, l - 1);
+            void* out = l == n_layers - 1 ? y[m] : p.act(m, l);
+            TRY(layer_fwd_impl(ctx, d, cfg, &w[l], in, out, p.saved(m, l), workspace, st));
+        }
+    void* gbuf = at(workspace, work_layout(d).total);  // gradient flowing between layers, updated in place
+    for (int m = 0; m < n_micro; m++)
+        for (int l = n_layers - 1; l >= 0; l--) {
+            const void* in = l == 0 ? x[m] : p.act(m, l - 1);
+            const void* gin = l == n_layers - 1 ? dy[m] : gbuf;
+            void* gout = l == 0 ? dx[m] : gbuf;
+            const int acc = (m > 0 || !zero_grads_first) ? 1 : 0;
+            TRY(layer_bwd_impl(ctx, d, cfg, &w[l], in, p.saved(m, l), gin, gout, &g[l], acc, workspace, st));
+        }
+    return HH_OK;
+}
+
+// ------------------------------------------------------------------ profile
+static float median(std::vector<float>& v) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return n % 2 ? v[n / 2] : 0.5f * (v[n / 2 - 1] + v[n / 2]);
+}
+
+extern "C" int hh_layer_profile(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w,
+                                const hh_layer_grads* g, const void* x, const void* dy, int warmup, int iters,
+                                void* saved_pool, void* workspace, hh_profile_rec* out, void* stream) {
+    TRY(check_stage_args(cfg, n_layers, w, g));
+    if (warmup < 0 || iters <= 0) return fail(HH_ERR_INVALID_ARG, "warmup must be >= 0 and iters > 0");
+    TRY(check_ptr(x, "x")); TRY(check_ptr(dy, "dy")); TRY(check_ptr(saved_pool, "saved_pool")); TRY(check_ptr(workspace, "workspace"));
+    if (!out) return fail(HH_ERR_INVALID_ARG, "out is NULL");
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    TRY(ensure_rope(ctx, cfg));
+    const Dims d = dims_of(cfg);
+    const StagePool p = stage_pool(d, n_layers, saved_pool);
+    hipStream_t st = (hipStream_t)stream;
+    void* gbuf = at(workspace, work_layout(d).total);
+    // the last layer's output has no slot in the pool (the caller's y in a stage step): park it in gbuf,
+    // which is free during the forward sweep
+    const int k = n_layers;
+    std::vector<hipEvent_t> ev((size_t)4 * k);
+    for (auto& e : ev) e = nullptr;
+    int rc = HH_OK;
+    auto cleanup = [&]() { for (auto e : ev) if (e) (void)hipEventDestroy(e); };
+    for (auto& e : ev) {
+        hipError_t he = hipEventCreate(&e);
+        if (he != hipSuccess) { cleanup(); return hip_fail(he, "hipEventCreate"); }
+    }
+    std::vector<std::vector<float>> tf(k), tb(k);
+    for (int it = 0; it < warmup + iters && rc == HH_OK; it++) {
+        for (int l = 0; l < k && rc == HH_OK; l++) {
+            const void* in = l == 0 ? x : p.act(0, l - 1);
+            void* o = l == k - 1 ? gbuf : p.act(0, l);
+            (void)hipEventRecord(ev[4 * l], st);
+            rc = layer_fwd_impl(ctx, d, cfg, &w[l], in, o, p.saved(0, l), workspace, st);
+            (void)hipEventRecord(ev[4 * l + 1], st);
+        }
+        for (int l = k - 1; l >= 0 && rc == HH_OK; l--) {
+            const void* in = l == 0 ? x : p.act(0, l - 1);
+            const void* gin = l == k - 1 ? dy : gbuf;
+            (void)hipEventRecord(ev[4 * l + 2], st);
+            rc = layer_bwd_impl(ctx, d, cfg, &w[l], in, p.saved(0, l), gin, gbuf, &g[l], 1, workspace, st);
+            (void)hipEventRecord(ev[4 * l + 3], st);
+        }
+        if (rc != HH_OK) break;
+        hipError_t he = hipStreamSynchronize(st);
+        if (he != hipSuccess) { rc = hip_fail(he, "hipStreamSynchronize"); break; }
+        if (it >= warmup)
+            for (int l = 0; l < k; l++) {
+                float a = 0.f, b = 0.f;
+                (void)hipEventElapsedTime(&a, ev[4 * l], ev[4 * l + 1]);
+                (void)hipEventElapsedTime(&b, ev[4 * l + 2], ev[4 * l + 3]);
+                tf[l].push_back(a);
+                tb[l].push_back(b);
+            }
+    }
+    cleanup();
+    if (rc != HH_OK) return rc;
+    double ff = 0, bf = 0;
+    (void)hh_layer_flops(cfg, &ff, &bf);
+    const size_t A = d.A;
+    const uint64_t nparam = 2ull * d.H + 4ull * A * d.H + 3ull * (uint64_t)d.F * d.H;
+    for (int l = 0; l < k; l++) {
+        hh_profile_rec& r = out[l];
+        r.layer = l;
+        r.fwd_ms = median(tf[l]);
+        r.bwd_ms = median(tb[l]);
+        r.fwd_flop = ff; r.bwd_flop = bf;
+        r.fwd_tflops = (float)(ff / (r.fwd_ms * 1e-3) * 1e-12);
+        r.bwd_tflops = (float)(bf / (r.bwd_ms * 1e-3) * 1e-12);
+        r.weight_bytes = nparam * d.es;
+        r.grad_bytes = nparam * 4;
+        r.saved_act_bytes = p.saved_sz + (uint64_t)d.T * d.H * d.es;  // the saved block plus the layer's input
+        r.p2p_bytes = (uint64_t)d.B * d.S * d.H * 2;
+    }
+    return HH_OK;
+}

@@ -22,6 +22,8 @@ residual hide errors), activations and upstream gradients are N(0, 1).
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
 import numpy as np
@@ -51,21 +53,31 @@ def _mix64(z: np.ndarray) -> np.ndarray:
     return z ^ (z >> np.uint64(31))
 
 
+def _normal_chunk(out: np.ndarray, key: int, lo: int, hi: int, scale: float, mean: float) -> None:
+    two53 = 2.0 ** -53
+    with np.errstate(over="ignore"):
+        c = np.arange(2 * lo, 2 * hi, 2, dtype=np.uint64) + np.uint64(key)
+        u1 = ((_mix64(c) >> np.uint64(11)).astype(np.float64) + 1.0) * two53
+        u2 = (_mix64(c + np.uint64(1)) >> np.uint64(11)).astype(np.float64) * two53
+        z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+        out[lo:hi] = (mean + scale * z).astype(np.float32)
+
+
 def normal(seed: int, tid: int, shape, scale: float = 1.0, mean: float = 0.0,
-           chunk: int = 1 << 22) -> np.ndarray:
-    """fp32 array of ``shape`` with entries mean + scale * N(0,1); see module doc."""
+           chunk: int = 1 << 20) -> np.ndarray:
+    """fp32 array of ``shape`` with entries mean + scale * N(0,1); see module doc.
+    Elements are independent of the chunking (large draws are filled by a few threads)."""
     n = int(np.prod(shape)) if len(tuple(shape)) else 1
     out = np.empty(n, dtype=np.float32)
     key = _mix64_int(_mix64_int(seed) + tid)
-    two53 = 2.0 ** -53
-    with np.errstate(over="ignore"):
-        for lo in range(0, n, chunk):
-            hi = min(n, lo + chunk)
-            c = np.arange(2 * lo, 2 * hi, 2, dtype=np.uint64) + np.uint64(key)
-            u1 = ((_mix64(c) >> np.uint64(11)).astype(np.float64) + 1.0) * two53
-            u2 = (_mix64(c + np.uint64(1)) >> np.uint64(11)).astype(np.float64) * two53
-            z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-            out[lo:hi] = (mean + scale * z).astype(np.float32)
+    spans = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+    if len(spans) <= 2:
+        for lo, hi in spans:
+            _normal_chunk(out, key, lo, hi, scale, mean)
+    else:
+        nthreads = max(1, min(16, os.cpu_count() or 1))
+        with ThreadPoolExecutor(nthreads) as ex:
+            list(ex.map(lambda sp: _normal_chunk(out, key, sp[0], sp[1], scale, mean), spans))
     return out.reshape(shape)
 
 

@@ -1,0 +1,142 @@
+"""The C-ABI library: loads, exports what include/hh.h declares, validates arguments
+before touching a GPU, and its host-side size / flop arithmetic.  Runs without a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2405_16256_amd import binding as hh
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "hh.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(hh_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(hh.EXPORTS), names
+    for n in names:
+        assert getattr(hh.lib, n) is not None
+
+
+def cfg3():
+    return hh.make_cfg(12288, 12, 128, 4096, 4096, 1)
+
+
+def test_flops_match_the_model_flop_convention():
+    f, b = hh.hh_layer_flops(cfg3())
+    # GEMM 2mnk: per token 8AH + 6HF; causal attention 4 d per (query, key <= query) pair
+    T, H, A, F, S, nh, d = 4096, 12288, 1536, 4096, 4096, 12, 128
+    gemm = T * (8 * A * H + 6 * H * F)
+    attn = 4 * d * nh * S * (S + 1) // 2
+    assert f == gemm + attn and b == 2 * f
+    assert abs((f + b) - 5.721e12) / 5.721e12 < 1e-3
+    f2, b2 = hh.hh_layer_flops(hh.make_cfg(4096, 32, 128, 11008, 2048, 1))
+    assert abs((f2 + b2) - 2.590e12) / 2.590e12 < 1e-3
+    f1, b1 = hh.hh_layer_flops(hh.make_cfg(256, 4, 64, 688, 128, 1, dtype=hh.HH_F32))
+    assert abs((f1 + b1) - 6.325e8) / 6.325e8 < 1e-3
+
+
+def test_sizes():
+    saved, ws = hh.hh_layer_sizes(cfg3())
+    T, H, A, F = 4096, 12288, 1536, 4096
+    # xn, h, hn [T,H]; qkv [T,3A]; a [T,A]; gate|up [T,2F]; lse, r1, r2 fp32
+    expect = 2 * (3 * T * H + 3 * T * A + T * A + 2 * T * F) + 4 * (12 * 4096 + 2 * T)
+    assert expect <= saved <= expect + 16 * 256
+    assert ws > 0 and ws % 256 == 0
+    pool, ws2 = hh.hh_stage_sizes(cfg3(), 4, 8)
+    assert pool == 8 * (4 * saved + 3 * 2 * T * H)
+    assert ws2 == ws + 2 * T * H
+    s32, _ = hh.hh_layer_sizes(hh.make_cfg(256, 4, 64, 688, 128, 1, dtype=hh.HH_F32))
+    s16, _ = hh.hh_layer_sizes(hh.make_cfg(256, 4, 64, 704, 128, 1, dtype=hh.HH_BF16))
+    assert s32 > s16
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=96), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    (dict(hidden=4100), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    (dict(ffn=11000), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    (dict(n_kv_heads=8), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    (dict(seq=0), hh.HH_ERR_INVALID_ARG),
+    (dict(micro_batch=-1), hh.HH_ERR_INVALID_ARG),
+    (dict(dtype=7), hh.HH_ERR_INVALID_ARG),
+    (dict(rope_base=0.0), hh.HH_ERR_INVALID_ARG),
+    (dict(seq=1 << 20), hh.HH_ERR_UNSUPPORTED_SHAPE),
+])
+def test_cfg_validation(kw, code):
+    base = dict(hidden=4096, n_heads=32, head_dim=128, ffn=11008, seq=2048, micro_batch=1)
+    base.update(kw)
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_sizes(hh.make_cfg(**base))
+    assert e.value.code == code
+    assert hh.hh_last_error() != ""
+
+
+def test_fp32_accepts_multiples_of_8_bf16_does_not():
+    hh.hh_layer_sizes(hh.make_cfg(256, 4, 64, 688, 128, 1, dtype=hh.HH_F32))
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_sizes(hh.make_cfg(256, 4, 64, 688, 128, 1, dtype=hh.HH_BF16))
+    assert e.value.code == hh.HH_ERR_UNSUPPORTED_SHAPE
+
+
+def test_pointer_validation_happens_before_any_gpu_work():
+    cfg = hh.make_cfg(256, 4, 64, 704, 128, 1)
+    ok = 4096  # an aligned, never dereferenced address
+    w = hh.hh_layer_weights(*([ok] * 9))
+    g = hh.hh_layer_grads(*([ok] * 9))
+    # NULL tensor
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_fwd(None, cfg, w, None, ok * 2, ok, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "x" in str(e.value)
+    # misaligned tensor
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_fwd(None, cfg, w, ok + 8, ok * 2, ok, ok)
+    assert e.value.code == hh.HH_ERR_MISALIGNED
+    # y aliases x
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_fwd(None, cfg, w, ok, ok, ok, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "alias" in str(e.value)
+    # NULL weight
+    wbad = hh.hh_layer_weights(*([ok] * 4 + [None] + [ok] * 4))
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_fwd(None, cfg, wbad, ok, ok * 2, ok, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "wo" in str(e.value)
+    # misaligned gradient
+    gbad = hh.hh_layer_grads(*([ok] * 8 + [ok + 4]))
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_bwd(None, cfg, w, ok, ok, ok, ok, gbad, 0, ok)
+    assert e.value.code == hh.HH_ERR_MISALIGNED
+    # everything valid except the context: reported last
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_bwd(None, cfg, w, ok, ok, ok, ok, g, 0, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "ctx" in str(e.value)
+    # stage step
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_stage_step(None, cfg, [w], [ok], [ok], [ok], [ok], [g], 1, ok, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "alias" in str(e.value)
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_stage_step(None, cfg, [w], [ok], [2 * ok], [ok], [ok], [g], 1, None, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "saved_pool" in str(e.value)
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_stage_sizes(cfg, 0, 1)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_layer_profile(None, cfg, [w], [g], ok, ok, 0, 0, ok, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG
+
+
+def test_ctx_create_reports_missing_device():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_ctx_create(0)
+    assert e.value.code == hh.HH_ERR_DEVICE
+    out = C.c_void_p()
+    assert hh.lib.hh_ctx_create(None, 0) == hh.HH_ERR_INVALID_ARG
+    assert hh.lib.hh_ctx_destroy(None) == hh.HH_OK
