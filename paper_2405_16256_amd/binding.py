@@ -10,6 +10,11 @@ import ctypes as C
 import os
 from typing import Sequence
 
+# PyTorch-ROCm ships its own HIP runtime.  It has to be in the process before libhh.so is
+# opened so that the library binds to that same runtime (one runtime per process: streams
+# and device pointers are shared with torch).
+import torch  # noqa: F401
+
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhh.so")
 
 HH_OK = 0

@@ -290,7 +290,7 @@ static int layer_fwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
         for (int i = 0; i < 3; i++)
             HIP_TRY(gemm(dt, desc(GEMM_NT, T, A, H, xn, H, ws3[i], H, at(qkv, (size_t)i * A * es), 3 * A), st));
     }
-    HIP_TRY(rope(dt, qkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, 0, st));
+    HIP_TRY(rope(dt, qkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 0, st));
     HIP_TRY(attn_fwd(dt, qkv, 3 * A, a, lse, d.B, d.S, d.nh, d.d, st));
     HIP_TRY(gemm(dt, desc(GEMM_NT, T, H, A, a, A, w->wo, A, h, H, x, H), st));
     HIP_TRY(rmsnorm_fwd(dt, h, w->g_mlp, hn, r2, T, H, cfg->rms_eps, st));
@@ -369,7 +369,7 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     HIP_TRY(gemm(dt, desc(GEMM_TN, H, A, T, dh, H, a, A, g->wo, A, nullptr, 0, 1, acc), st));
     HIP_TRY(gemm(dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
     HIP_TRY(attn_bwd(dt, qkv, 3 * A, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.d, st));
-    HIP_TRY(rope(dt, dqkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, 1, st));
+    HIP_TRY(rope(dt, dqkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
                             (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
     const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)A * H * 4;

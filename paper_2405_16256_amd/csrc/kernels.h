@@ -38,8 +38,9 @@ hipError_t rmsnorm_bwd(int dtype, const void* dxn, const void* x, const float* r
 hipError_t colsum_reduce(const float* partial, int nblk, int H, float* out, int accumulate, hipStream_t st);
 
 // In-place rotary embedding of the q and k column blocks of a [T, ld] buffer
-// (q at column 0, k at column nh*d).  table[S][d/2][2] = (cos, sin).  backward: rotate by -angle.
-hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nh, int d, const float* table,
+// (q at column 0, k at column nh*d).  table = cos[table_seq][d/2] followed by sin[table_seq][d/2],
+// table_seq >= S.  backward: rotate by -angle.
+hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nh, int d, const float* table, int table_seq,
                 int backward, hipStream_t st);
 
 // gu[T,2F] = (gate | up);  m = silu(gate)*up

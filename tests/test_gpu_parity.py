@@ -61,8 +61,10 @@ def check_layer(ctx, s, bf16, seed, packed=True, label=""):
     for n, e in errs.items():
         if n != "y":
             assert e <= tol_grad, (n, errs)
-    # the residual must not hide a broken branch
-    assert branch <= (0.1 if bf16 else 1e-3), branch
+    # the residual must not hide a broken branch: y - x is judged against its own norm, allowing for
+    # the rounding of the bf16 residual stream (3 half-ulps of y, which is large next to a small branch)
+    floor = 3.0 * 2.0 ** -9 * np.linalg.norm(yo) / np.linalg.norm(yo - x)
+    assert branch <= (max(0.05, floor) if bf16 else 1e-3), (branch, floor)
     return errs
 
 
