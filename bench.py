@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Decoder-layer forward+backward throughput on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+hh_stage_step over the workload's layers and micro-batches (for the default
+workload, one 140B-class TP=8-share decoder layer, one micro-batch of 4096
+tokens: forward, then backward with fp32 gradient accumulation), every kernel
+hand-written HIP behind the C-ABI.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
+
+
+def workloads():
+    from paper_2405_16256_amd import inputs as I
+    return {
+        "cfg2": dict(shape=I.CFG2, k=1, M=1, seed=I.SEEDS["cfg2"],
+                     name="cfg2: 7B-class decoder layer, hidden 4096, 32x128 heads, ffn 11008, seq 2048, micro-batch 1, bf16 fwd+bwd"),
+        "cfg3": dict(shape=I.CFG3, k=1, M=1, seed=I.SEEDS["cfg3"],
+                     name="cfg3: 140B-class decoder layer at a TP=8 share, hidden 12288, 12x128 local heads, local ffn 4096, "
+                          "seq 4096, micro-batch 1, bf16 fwd+bwd"),
+        "cfg4": dict(shape=I.CFG3, k=4, M=8, seed=I.SEEDS["cfg4"],
+                     name="cfg4: pipeline-stage step, 4 layers of the cfg3 shape x 8 micro-batches of seq 4096, fp32 grad accumulation"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % a.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2405_16256_amd import binding as hh
+    from paper_2405_16256_amd import inputs as I
+    from paper_2405_16256_amd import glue as L
+
+    wl = workloads()[a.workload]
+    s, k, M, seed = wl["shape"], wl["k"], wl["M"], wl["seed"]
+    torch.cuda.set_device(0)
+    cfg = L.cfg_of(s, True)
+    ctx = hh.hh_ctx_create(0)
+    hh.hh_ctx_reserve(ctx, cfg)
+
+    t0 = time.time()
+    w_np = [I.layer_weights(seed, l, s, True) for l in range(k)]
+    layers = [L.DeviceLayer(w, s, True) for w in w_np]
+    acts = [I.activations(seed, s, m, True) for m in range(min(M, 2))]   # micro-batches beyond 2 reuse these draws
+    xs = [L.to_dev(acts[m % len(acts)][0], True) for m in range(M)]
+    dys = [L.to_dev(acts[m % len(acts)][1], True) for m in range(M)]
+    ys = [torch.empty_like(t) for t in xs]
+    dxs = [torch.empty_like(t) for t in xs]
+    pool_b, ws_b = hh.hh_stage_sizes(cfg, k, M)
+    pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
+    wsp = torch.empty(ws_b, dtype=torch.uint8, device=L.DEV)
+    print("[bench] inputs ready in %.1fs; pool %.2f GB" % (time.time() - t0, pool_b / 1e9), file=sys.stderr, flush=True)
+
+    wst, gst = [l.wstruct for l in layers], [l.gstruct for l in layers]
+    st = L.stream_ptr()
+
+    def step():
+        # steady-state training: gradients accumulate, nothing is zeroed inside the timed region
+        hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    hh.hh_trace_begin(ctx, a.steps * k * M * 40)
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fam = hh.hh_trace_end(ctx)
+
+    f, b = hh.hh_layer_flops(cfg)
+    flop_step = (f + b) * k * M
+    ms = dt / a.steps * 1e3
+    tflops = flop_step / (dt / a.steps) / 1e12
+    tokens_s = s.tokens * M / (dt / a.steps)
+
+    gemms = {n: v for n, v in fam.items() if n.startswith("gemm") and v[0] > 0}
+    dom = max(gemms, key=lambda n: gemms[n][1])
+    launches, dms, dwork = gemms[dom]
+    achieved = dwork / (dms * 1e-3) / 1e12
+    breakdown = {n: {"launches": v[0], "ms_per_step": round(v[1] / a.steps, 4),
+                     ("GB_per_s" if n == "elementwise" else "tflops"): round(v[2] / (v[1] * 1e-3) / (1e9 if n == "elementwise" else 1e12), 1)}
+                 for n, v in fam.items() if v[0] > 0}
+
+    out = {
+        "metric": "decoder-layer fwd+bwd TFLOP/s on 1 GPU", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl["name"], "layers": k, "micro_batches": M, "tokens_per_micro_batch": s.tokens,
+                   "model_flop_per_step": flop_step},
+        "tokens_per_s": round(tokens_s, 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"kernel": "k_gemm_bf16 (%s)" % dom, "bound": "mfma", "achieved": round(achieved, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "launches": launches, "avg_launch_ms": round(dms / launches, 4),
+                     "flop_per_launch": dwork / launches},
+        "kernel_families": breakdown,
+    }
+
+    if not a.no_cpu_baseline:
+        # the oracle, as it stands, on the host cores: one full layer forward+backward of the same workload
+        from oracle import decoder_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        x0, dy0 = acts[0]
+        t0 = time.perf_counter()
+        yo, cache = O.layer_forward(x0, w_np[0], s.n_heads, s.head_dim, s.rms_eps, s.rope_base)
+        dxo, go = O.layer_backward(dy0, w_np[0], cache)
+        ct = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round((f + b) / ct / 1e12, 4), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                               "sample": "one layer x one micro-batch of the same workload (fp64, %.1f s)" % ct}
+        # the run also serves as an end-to-end parity check of the timed configuration
+        err = L.rel_err(L.to_np(ys[0]), yo) if k == 1 else None
+        out["parity_y_rel_fro"] = None if err is None else float("%.3e" % err)
+    print(json.dumps(out), flush=True)
+    hh.hh_ctx_destroy(ctx)
+
+
+if __name__ == "__main__":
+    main()

@@ -177,6 +177,32 @@ int hh_layer_profile(hh_ctx *ctx, const hh_layer_cfg *cfg, int n_layers, const h
                      int warmup, int iters, void *saved_pool, void *workspace,
                      hh_profile_rec *out, void *stream);
 
+/* Per-kernel-family timing of whatever the hot calls enqueue (the measurement
+ * side of the automatic profiling of Section 3.2).  Between hh_trace_begin and
+ * hh_trace_end every launch is bracketed by HIP events on its stream, up to
+ * max_launches launches (later ones are not recorded).  hh_trace_begin creates
+ * the events (not a hot call); hh_trace_end waits for them and fills
+ * out[0..n_kinds-1] (HOST) with launch count, summed milliseconds and summed
+ * work: model flops for GEMM and attention families, algorithmic bytes for the
+ * elementwise family. */
+typedef enum {
+    HH_TRACE_GEMM_NT = 0,      /* forward projections       y  = x W^T   */
+    HH_TRACE_GEMM_NN = 1,      /* input gradients           dX = dY W    */
+    HH_TRACE_GEMM_TN = 2,      /* weight gradients          dW = dY^T X  */
+    HH_TRACE_ATTN_FWD = 3,
+    HH_TRACE_ATTN_BWD = 4,
+    HH_TRACE_ELEMENTWISE = 5,  /* RMSNorm, RoPE, SwiGLU, gain-gradient reduction */
+    HH_TRACE_KINDS = 6
+} hh_trace_kind;
+typedef struct {
+    int32_t kind;
+    int32_t launches;
+    double ms;
+    double work;
+} hh_trace_sum;
+int hh_trace_begin(hh_ctx *ctx, int max_launches);
+int hh_trace_end(hh_ctx *ctx, hh_trace_sum *out, int n_kinds);
+
 #ifdef __cplusplus
 }
 #endif

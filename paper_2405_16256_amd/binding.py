@@ -28,7 +28,9 @@ HH_BF16 = 1
 
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
-           "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_layer_profile")
+           "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_layer_profile", "hh_trace_begin",
+           "hh_trace_end")
+TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
 
 class hh_layer_cfg(C.Structure):
@@ -50,6 +52,10 @@ class hh_profile_rec(C.Structure):
                 ("bwd_flop", C.c_double), ("fwd_tflops", C.c_float), ("bwd_tflops", C.c_float),
                 ("weight_bytes", C.c_uint64), ("grad_bytes", C.c_uint64), ("saved_act_bytes", C.c_uint64),
                 ("p2p_bytes", C.c_uint64)]
+
+
+class hh_trace_sum(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("launches", C.c_int32), ("ms", C.c_double), ("work", C.c_double)]
 
 
 class HHError(RuntimeError):
@@ -78,6 +84,8 @@ def _load() -> C.CDLL:
         "hh_stage_sizes": [cfgp, i, i, sz, sz],
         "hh_stage_step": [vp, cfgp, i, wp, i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), gp, i, vp, vp, vp],
         "hh_layer_profile": [vp, cfgp, i, wp, gp, vp, vp, i, i, vp, vp, C.POINTER(hh_profile_rec), vp],
+        "hh_trace_begin": [vp, i],
+        "hh_trace_end": [vp, C.POINTER(hh_trace_sum), i],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -184,3 +192,14 @@ def hh_layer_profile(ctx, cfg, weights: Sequence[hh_layer_weights], grads: Seque
     _check(lib.hh_layer_profile(ctx, C.byref(cfg), k, warr, garr, _ptr(x), _ptr(dy), warmup, iters, _ptr(saved_pool),
                                 _ptr(workspace), out, stream))
     return list(out)
+
+
+def hh_trace_begin(ctx, max_launches: int) -> None:
+    _check(lib.hh_trace_begin(ctx, max_launches))
+
+
+def hh_trace_end(ctx) -> dict:
+    """{family: (launches, total_ms, total_work)} for the launches since hh_trace_begin."""
+    out = (hh_trace_sum * len(TRACE_KINDS))()
+    _check(lib.hh_trace_end(ctx, out, len(TRACE_KINDS)))
+    return {TRACE_KINDS[r.kind]: (r.launches, r.ms, r.work) for r in out}

@@ -62,11 +62,19 @@ static int hip_fail(hipError_t e, const char* what) {
 extern "C" const char* hh_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ context
+struct TraceRec {
+    hipEvent_t a, b;
+    int kind;
+    double work;
+};
 struct hh_ctx {
     int device;
     float* rope_table;  // device: cos[S][d/2] then sin[S][d/2]
     int rope_seq, rope_dim;
     float rope_base;
+    std::vector<TraceRec> trace;  // events created by hh_trace_begin
+    size_t trace_used;
+    bool trace_on;
 };
 
 extern "C" int hh_ctx_create(hh_ctx** out, int device) {
@@ -76,7 +84,7 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess) return hip_fail(e, "hipGetDeviceCount");
     if (device < 0 || device >= n) return fail(HH_ERR_DEVICE, "hh_ctx_create: no HIP device %d (%d visible)", device, n);
-    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f};
+    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false};
     if (!c) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out of host memory");
     *out = c;
     return HH_OK;
@@ -85,6 +93,7 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
 extern "C" int hh_ctx_destroy(hh_ctx* ctx) {
     if (!ctx) return HH_OK;
     if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+    for (auto& r : ctx->trace) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete ctx;
     return HH_OK;
 }
@@ -257,6 +266,64 @@ extern "C" int hh_ctx_reserve(hh_ctx* ctx, const hh_layer_cfg* cfg) {
     return ensure_rope(ctx, cfg);
 }
 
+// ------------------------------------------------------------------ tracing
+// When tracing is on, every kernel-family launch is bracketed by two events on the
+// launch stream; hh_trace_end turns them into per-family time and work sums.
+struct Traced {
+    hh_ctx* ctx; hipStream_t st; TraceRec* rec;
+    Traced(hh_ctx* c, hipStream_t s, int kind, double work) : ctx(c), st(s), rec(nullptr) {
+        if (c->trace_on && c->trace_used < c->trace.size()) {
+            rec = &c->trace[c->trace_used++];
+            rec->kind = kind; rec->work = work;
+            (void)hipEventRecord(rec->a, st);
+        }
+    }
+    ~Traced() { if (rec) (void)hipEventRecord(rec->b, st); }
+};
+#define TR(kind, work, call)                     \
+    do {                                         \
+        Traced t_(ctx, st, (kind), (double)(work)); \
+        HIP_TRY(call);                           \
+    } while (0)
+static double attn_flop(const Dims& d) { return 4.0 * d.d * d.B * d.nh * ((double)d.S * (d.S + 1) / 2); }
+static double gemm_flop(const GemmDesc& g) { return 2.0 * g.M * g.N * g.K; }
+static hipError_t tgemm(hh_ctx* ctx, int dt, const GemmDesc& g, hipStream_t st) {
+    Traced t(ctx, st, g.kind, gemm_flop(g));
+    return gemm(dt, g, st);
+}
+
+extern "C" int hh_trace_begin(hh_ctx* ctx, int max_launches) {
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    if (max_launches <= 0) return fail(HH_ERR_INVALID_ARG, "max_launches must be positive");
+    HIP_TRY(hipSetDevice(ctx->device));
+    while ((int)ctx->trace.size() < max_launches) {
+        TraceRec r{nullptr, nullptr, 0, 0.0};
+        HIP_TRY(hipEventCreate(&r.a));
+        hipError_t e = hipEventCreate(&r.b);
+        if (e != hipSuccess) { (void)hipEventDestroy(r.a); return hip_fail(e, "hipEventCreate"); }
+        ctx->trace.push_back(r);
+    }
+    ctx->trace_used = 0;
+    ctx->trace_on = true;
+    return HH_OK;
+}
+
+extern "C" int hh_trace_end(hh_ctx* ctx, hh_trace_sum* out, int n_kinds) {
+    if (!ctx || !out) return fail(HH_ERR_INVALID_ARG, "ctx or out is NULL");
+    if (n_kinds <= 0) return fail(HH_ERR_INVALID_ARG, "n_kinds must be positive");
+    ctx->trace_on = false;
+    for (int k = 0; k < n_kinds; k++) { out[k].kind = k; out[k].launches = 0; out[k].ms = 0.0; out[k].work = 0.0; }
+    for (size_t i = 0; i < ctx->trace_used; i++) {
+        const TraceRec& r = ctx->trace[i];
+        HIP_TRY(hipEventSynchronize(r.b));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+        if (r.kind < n_kinds) { out[r.kind].launches++; out[r.kind].ms += ms; out[r.kind].work += r.work; }
+    }
+    ctx->trace_used = 0;
+    return HH_OK;
+}
+
 // ------------------------------------------------------------ layer forward
 static inline char* at(void* base, size_t off) { return (char*)base + off; }
 static inline const char* at(const void* base, size_t off) { return (const char*)base + off; }
@@ -280,29 +347,29 @@ static int layer_fwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     float* lse = (float*)at(saved, sl.lse); float* r1 = (float*)at(saved, sl.r1); float* r2 = (float*)at(saved, sl.r2);
     void* m = at(ws, wl.m);
 
-    HIP_TRY(rmsnorm_fwd(dt, x, w->g_attn, xn, r1, T, H, cfg->rms_eps, st));
+    TR(HH_TRACE_ELEMENTWISE, 2.0 * T * H * es, rmsnorm_fwd(dt, x, w->g_attn, xn, r1, T, H, cfg->rms_eps, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
                             (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
     if (qkv_packed) {
-        HIP_TRY(gemm(dt, desc(GEMM_NT, T, 3 * A, H, xn, H, w->wq, H, qkv, 3 * A), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, 3 * A, H, xn, H, w->wq, H, qkv, 3 * A), st));
     } else {
         const void* ws3[3] = {w->wq, w->wk, w->wv};
         for (int i = 0; i < 3; i++)
-            HIP_TRY(gemm(dt, desc(GEMM_NT, T, A, H, xn, H, ws3[i], H, at(qkv, (size_t)i * A * es), 3 * A), st));
+            HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, A, H, xn, H, ws3[i], H, at(qkv, (size_t)i * A * es), 3 * A), st));
     }
-    HIP_TRY(rope(dt, qkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 0, st));
-    HIP_TRY(attn_fwd(dt, qkv, 3 * A, a, lse, d.B, d.S, d.nh, d.d, st));
-    HIP_TRY(gemm(dt, desc(GEMM_NT, T, H, A, a, A, w->wo, A, h, H, x, H), st));
-    HIP_TRY(rmsnorm_fwd(dt, h, w->g_mlp, hn, r2, T, H, cfg->rms_eps, st));
+    TR(HH_TRACE_ELEMENTWISE, 4.0 * T * A * es, rope(dt, qkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 0, st));
+    TR(HH_TRACE_ATTN_FWD, attn_flop(d), attn_fwd(dt, qkv, 3 * A, a, lse, d.B, d.S, d.nh, d.d, st));
+    HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, H, A, a, A, w->wo, A, h, H, x, H), st));
+    TR(HH_TRACE_ELEMENTWISE, 2.0 * T * H * es, rmsnorm_fwd(dt, h, w->g_mlp, hn, r2, T, H, cfg->rms_eps, st));
     const bool gu_packed = (const char*)w->w_up == (const char*)w->w_gate + (size_t)F * H * es;
     if (gu_packed) {
-        HIP_TRY(gemm(dt, desc(GEMM_NT, T, 2 * F, H, hn, H, w->w_gate, H, gu, 2 * F), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, 2 * F, H, hn, H, w->w_gate, H, gu, 2 * F), st));
     } else {
-        HIP_TRY(gemm(dt, desc(GEMM_NT, T, F, H, hn, H, w->w_gate, H, gu, 2 * F), st));
-        HIP_TRY(gemm(dt, desc(GEMM_NT, T, F, H, hn, H, w->w_up, H, at(gu, (size_t)F * es), 2 * F), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, F, H, hn, H, w->w_gate, H, gu, 2 * F), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, F, H, hn, H, w->w_up, H, at(gu, (size_t)F * es), 2 * F), st));
     }
-    HIP_TRY(swiglu_fwd(dt, gu, m, T, F, st));
-    HIP_TRY(gemm(dt, desc(GEMM_NT, T, H, F, m, F, w->w_down, F, y, H, h, H), st));
+    TR(HH_TRACE_ELEMENTWISE, 3.0 * T * F * es, swiglu_fwd(dt, gu, m, T, F, st));
+    HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, H, F, m, F, w->w_down, F, y, H, h, H), st));
     return HH_OK;
 }
 
@@ -345,52 +412,52 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     acc = acc ? 1 : 0;
 
     // MLP branch: y = h + m Wd^T
-    HIP_TRY(gemm(dt, desc(GEMM_NN, T, F, H, dy, H, w->w_down, F, m, F), st));                 // dm (in the m buffer)
-    HIP_TRY(swiglu_bwd(dt, m, gu, dgu, m, T, F, st));                                          // dgate|dup, m
-    HIP_TRY(gemm(dt, desc(GEMM_TN, H, F, T, dy, H, m, F, g->w_down, F, nullptr, 0, 1, acc), st));
+    HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, F, H, dy, H, w->w_down, F, m, F), st));                 // dm (in the m buffer)
+    TR(HH_TRACE_ELEMENTWISE, 6.0 * T * F * es, swiglu_bwd(dt, m, gu, dgu, m, T, F, st));                                          // dgate|dup, m
+    HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, H, F, T, dy, H, m, F, g->w_down, F, nullptr, 0, 1, acc), st));
     const bool gu_packed = (const char*)w->w_up == (const char*)w->w_gate + (size_t)F * H * es;
     const bool dgu_packed = (char*)g->w_up == (char*)g->w_gate + (size_t)F * H * 4;
     if (dgu_packed) {
-        HIP_TRY(gemm(dt, desc(GEMM_TN, 2 * F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, 2 * F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
     } else {
-        HIP_TRY(gemm(dt, desc(GEMM_TN, F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
-        HIP_TRY(gemm(dt, desc(GEMM_TN, F, H, T, at(dgu, (size_t)F * es), 2 * F, hn, H, g->w_up, H, nullptr, 0, 1, acc), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, F, H, T, at(dgu, (size_t)F * es), 2 * F, hn, H, g->w_up, H, nullptr, 0, 1, acc), st));
     }
     if (gu_packed) {
-        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, 2 * F, dgu, 2 * F, w->w_gate, H, dhn, H), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, 2 * F, dgu, 2 * F, w->w_gate, H, dhn, H), st));
     } else {
-        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, F, dgu, 2 * F, w->w_gate, H, dhn, H), st));
-        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, F, at(dgu, (size_t)F * es), 2 * F, w->w_up, H, dhn, H, dhn, H), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, F, dgu, 2 * F, w->w_gate, H, dhn, H), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, F, at(dgu, (size_t)F * es), 2 * F, w->w_up, H, dhn, H, dhn, H), st));
     }
-    HIP_TRY(rmsnorm_bwd(dt, dhn, h, r2, w->g_mlp, dy, dh, partial, T, H, st));                // dh = dy + norm-bwd
-    HIP_TRY(colsum_reduce(partial, nblk, H, g->g_mlp, acc, st));
+    TR(HH_TRACE_ELEMENTWISE, 4.0 * T * H * es, rmsnorm_bwd(dt, dhn, h, r2, w->g_mlp, dy, dh, partial, T, H, st));                // dh = dy + norm-bwd
+    TR(HH_TRACE_ELEMENTWISE, 4.0 * nblk * H, colsum_reduce(partial, nblk, H, g->g_mlp, acc, st));
 
     // attention branch: h = x + a Wo^T
-    HIP_TRY(gemm(dt, desc(GEMM_TN, H, A, T, dh, H, a, A, g->wo, A, nullptr, 0, 1, acc), st));
-    HIP_TRY(gemm(dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
-    HIP_TRY(attn_bwd(dt, qkv, 3 * A, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.d, st));
-    HIP_TRY(rope(dt, dqkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
+    HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, H, A, T, dh, H, a, A, g->wo, A, nullptr, 0, 1, acc), st));
+    HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
+    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, 3 * A, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.d, st));
+    TR(HH_TRACE_ELEMENTWISE, 4.0 * T * A * es, rope(dt, dqkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
                             (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
     const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)A * H * 4;
     if (dqkv_packed) {
-        HIP_TRY(gemm(dt, desc(GEMM_TN, 3 * A, H, T, dqkv, 3 * A, xn, H, g->wq, H, nullptr, 0, 1, acc), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, 3 * A, H, T, dqkv, 3 * A, xn, H, g->wq, H, nullptr, 0, 1, acc), st));
     } else {
         float* gs[3] = {g->wq, g->wk, g->wv};
         for (int i = 0; i < 3; i++)
-            HIP_TRY(gemm(dt, desc(GEMM_TN, A, H, T, at(dqkv, (size_t)i * A * es), 3 * A, xn, H, gs[i], H, nullptr, 0, 1, acc), st));
+            HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, A, H, T, at(dqkv, (size_t)i * A * es), 3 * A, xn, H, gs[i], H, nullptr, 0, 1, acc), st));
     }
     void* dxn = dhn;
     if (qkv_packed) {
-        HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, 3 * A, dqkv, 3 * A, w->wq, H, dxn, H), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, 3 * A, dqkv, 3 * A, w->wq, H, dxn, H), st));
     } else {
         const void* ws3[3] = {w->wq, w->wk, w->wv};
         for (int i = 0; i < 3; i++)
-            HIP_TRY(gemm(dt, desc(GEMM_NN, T, H, A, at(dqkv, (size_t)i * A * es), 3 * A, ws3[i], H, dxn, H,
+            HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, A, at(dqkv, (size_t)i * A * es), 3 * A, ws3[i], H, dxn, H,
                                   i ? dxn : nullptr, H), st));
     }
-    HIP_TRY(rmsnorm_bwd(dt, dxn, x, r1, w->g_attn, dh, dx, partial, T, H, st));              // dx = dh + norm-bwd
-    HIP_TRY(colsum_reduce(partial, nblk, H, g->g_attn, acc, st));
+    TR(HH_TRACE_ELEMENTWISE, 4.0 * T * H * es, rmsnorm_bwd(dt, dxn, x, r1, w->g_attn, dh, dx, partial, T, H, st));              // dx = dh + norm-bwd
+    TR(HH_TRACE_ELEMENTWISE, 4.0 * nblk * H, colsum_reduce(partial, nblk, H, g->g_attn, acc, st));
     return HH_OK;
 }
 

@@ -1,4 +1,4 @@
-"""Helpers shared by the GPU parity tests, the smoke check and the benchmark:
+"""PyTorch plumbing shared by the GPU parity tests, the smoke check and the benchmark:
 moving seeded numpy inputs to the GPU, calling the C-ABI through the binding and
 bringing results back as fp64.  No arithmetic of the method lives here."""
 from __future__ import annotations

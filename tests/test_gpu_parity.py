@@ -15,7 +15,7 @@ import torch
 from oracle import decoder_oracle as O
 from paper_2405_16256_amd import binding as hh
 from paper_2405_16256_amd import inputs as I
-from tests import hh_testlib as L
+from paper_2405_16256_amd import glue as L
 
 pytestmark = pytest.mark.gpu
 
