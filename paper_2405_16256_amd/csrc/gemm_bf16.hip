@@ -5,22 +5,28 @@
 //   NN  C[M,N] = A[M,K] B[K,N]        backward dX = dY W
 //   TN  C[M,N] = A[K,M]^T B[K,N]      backward dW = dY^T X   (fp32 output, optional +=)
 //
-// One workgroup = 4 waves in a 2x2 grid computes a BM x BN tile of C with
-// v_mfma_f32_32x32x16_bf16; the k loop advances 64 at a time through two LDS
-// stages, the next tile's global loads (buffer loads: rows past the end of a
-// tensor read as zero) in flight while the current one feeds the matrix cores.
+// Two kernels, both on v_mfma_f32_32x32x16_bf16:
+//   * k_gemm_dma: 256x256 tile of C per workgroup of 8 waves (2 per SIMD, each a 128x64
+//     sub-tile), k advancing 32 at a time through four LDS stages that are filled straight
+//     from global memory (buffer_load ... lds), two tiles always in flight.  The loop is
+//     laid out by hand: MFMAs of one k step interleaved with the LDS fragment reads of the
+//     next and with the DMA issue of the tile three steps ahead.
+//   * k_gemm_bf16: 128x128 tile per workgroup of 4 waves, register-staged double buffer,
+//     for problems too small to fill the chip with 256x256 tiles.
 //
-// Operand tiles in LDS keep the layout they have in memory, so every global
-// load and LDS store is a 16-byte access:
-//   * k contiguous in memory  -> LDS [row][64 k], 16-byte chunks XOR-swizzled by
-//     the row index; fragments come out with ds_read_b128.
-//   * k strided in memory     -> LDS [64 k][rows], 64-byte slots XOR-swizzled by
-//     the k index; fragments come out with the transposing ds_read_b64_tr_b16.
+// Operand tiles in LDS keep the layout they have in memory, so global->LDS traffic is
+// 16 bytes per lane with no transposition:
+//   * k contiguous in memory  -> LDS [row][k], 16-byte chunks XOR-swizzled by the row
+//     index; fragments come out with ds_read_b128.
+//   * k strided in memory     -> LDS [k][rows], 64-byte slots XOR-swizzled by the k
+//     index; fragments come out with the transposing ds_read_b64_tr_b16.
 // Either way lane l of a fragment holds row (l % 32), k = 16*step + 8*(l/32) .. +7.
+// Rows past the end of a tensor read as zero (buffer bounds), so ragged token counts
+// need no special path.
 //
-// The MFMA takes the B-side fragment as its first operand, so each accumulator
-// lane owns one row m of C and runs of 4 consecutive columns n: stores are 8-byte
-// (bf16) or 16-byte (fp32) vectors along the contiguous dimension of C.
+// The MFMA takes the B-side fragment as its first operand, so each accumulator lane owns
+// one row m of C and runs of 4 consecutive columns n: stores are 8-byte (bf16) or 16-byte
+// (fp32) vectors along the contiguous dimension of C.
 #include "common.h"
 #include "kernels.h"
 
@@ -225,11 +231,213 @@ static hipError_t launch(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, 
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------
+// Large-tile kernel: 256x256 tile of C, k advances 32 at a time through FOUR LDS
+// stages that are filled straight from global memory (buffer_load ... lds: no
+// VGPR staging, no ds_write).  Tiles k+1, k+2 are in flight while tile k feeds the
+// matrix cores and tile k+3 is issued, so one tile has three compute phases to land.
+constexpr int DK = 32;           // k per stage
+constexpr int DSTAGES = 4;
+constexpr int DTILE = 256;
+constexpr int DSTAGE_BYTES = DTILE * DK * 2;   // one operand, one stage: 16 KB
+
+__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, i32x4 rs) {
+    // each lane moves 16 bytes from (rs.base + voff) to LDS byte (lds_addr + 16*lane); lanes past the
+    // buffer's extent deposit zeros
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rs) : "memory");
+}
+
+template <bool KC>
+struct DmaTile {
+    // Per wave and stage: 2 instructions of 1 KB (8 waves).  Instruction i of wave w covers
+    //   KC : rows 16*(2w+i) .. +15   (64 B per row, lane -> row L/4, physical chunk L%4)
+    //   KS : k rows 2*(4w+i), +1     (512 B per k row, lane -> k row L/32, physical chunk L%32)
+    // The global address picks the logical chunk that the swizzle places at that physical slot.
+    __device__ static __forceinline__ uint32_t voff(int i, int row0, int ld) {
+        const int w = threadIdx.x >> 6, L = threadIdx.x & 63;
+        if (KC) {
+            const int r = 16 * (2 * w + i) + (L >> 2);
+            const int logical = (L & 3) ^ ((r >> 2) & 3);
+            return ((uint32_t)(row0 + r) * (uint32_t)ld + (uint32_t)(logical * 8)) * 2u;
+        } else {
+            const int k = 2 * (2 * w + i) + (L >> 5);
+            const int lbyte = ((L & 31) * 16) ^ ((k & 3) << 6);
+            return ((uint32_t)k * (uint32_t)ld + (uint32_t)row0) * 2u + (uint32_t)lbyte;
+        }
+    }
+    __device__ static __forceinline__ uint32_t kstep_bytes(int ld) { return KC ? DK * 2u : (uint32_t)DK * (uint32_t)ld * 2u; }
+    // fragment of 32 rows starting at rb, k step kk (0,1)
+    __device__ static __forceinline__ bf16x8 frag(const char* lds, int rb, int kk) {
+        const int l = threadIdx.x & 63;
+        if (KC) {
+            const int r = rb + (l & 31), c = 2 * kk + (l >> 5);
+            return *reinterpret_cast<const bf16x8*>(lds + r * 64 + ((c ^ ((r >> 2) & 3)) << 4));
+        } else {
+            typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+            const int col = rb + 16 * ((l >> 4) & 1) + 4 * (l & 3);
+            const int kr0 = 16 * kk + 8 * (l >> 5) + ((l & 15) >> 2);
+            const int kr1 = kr0 + 4;
+            const char* p0 = lds + kr0 * (DTILE * 2) + ((col * 2) ^ ((kr0 & 3) << 6));
+            const char* p1 = lds + kr1 * (DTILE * 2) + ((col * 2) ^ ((kr1 & 3) << 6));
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p1);
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
+};
+
+template <int KIND, bool OUT_F32>
+__global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, int lda, uint32_t a_bytes,
+                                                       const bf16_t* __restrict__ B, int ldb, uint32_t b_bytes,
+                                                       void* __restrict__ Cv, int ldc, const bf16_t* R, int ldr,
+                                                       int M, int N, int K, int accumulate) {
+    constexpr bool A_KC = (KIND != GEMM_TN);
+    constexpr bool B_KC = (KIND == GEMM_NT);
+    using DA = DmaTile<A_KC>;
+    using DB = DmaTile<B_KC>;
+    constexpr int TM = 4, TN = 2;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [stage][A 16 KB | B 16 KB]
+
+    int tm, tn;
+    tile_of_block((M + DTILE - 1) / DTILE, (N + DTILE - 1) / DTILE, tm, tn);
+    const int m0 = tm * DTILE, n0 = tn * DTILE;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
+
+    const uint64_t pa = (uint64_t)A, pb = (uint64_t)B;
+    const i32x4 rsA = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)a_bytes, 0x00020000};
+    const i32x4 rsB = {(int)(uint32_t)pb, (int)(uint32_t)(pb >> 32), (int)b_bytes, 0x00020000};
+    uint32_t voA[2], voB[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++) { voA[i] = DA::voff(i, m0, lda); voB[i] = DB::voff(i, n0, ldb); }
+    const uint32_t stepA = DA::kstep_bytes(lda), stepB = DB::kstep_bytes(ldb);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * 2048);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+    const int nk = (K + DK - 1) / DK;
+#define SB() __builtin_amdgcn_sched_barrier(0)
+    // one DMA instruction of the k tile being issued (i < 4: A part i, else B part i-4) into stage st
+    auto dma_part = [&](int st, int i) {
+        const uint32_t base = wave_lds + st * (2 * DSTAGE_BYTES);
+        if (i < 2) { dma16(base + i * 1024, voA[i], rsA); voA[i] += stepA; }
+        else { dma16(base + DSTAGE_BYTES + (i - 2) * 1024, voB[i - 2], rsB); voB[i - 2] += stepB; }
+    };
+    // prologue: tiles 0, 1, 2 on their way; tile 0 landed; its first fragments in registers
+#pragma unroll
+    for (int s = 0; s < DSTAGES - 1; s++)
+        if (s < nk) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) dma_part(s, i);
+        }
+    if (nk > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (nk > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+#pragma unroll
+    for (int i = 0; i < TM; i++) a0[i] = DA::frag(smem, wm + 32 * i, 0);
+#pragma unroll
+    for (int j = 0; j < TN; j++) b0[j] = DB::frag(smem + DSTAGE_BYTES, wn + 32 * j, 0);
+
+    for (int kt = 0; kt < nk; kt++) {
+        // tile kt+1 must have landed (it is read before the next barrier); only tile kt+2 may be outstanding
+        if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // tile kt+1 complete in LDS for everyone; everyone is done reading tile kt-1
+        const char* cA = smem + (kt & 3) * (2 * DSTAGE_BYTES);
+        const char* cB = cA + DSTAGE_BYTES;
+        const char* nA = smem + ((kt + 1) & 3) * (2 * DSTAGE_BYTES);
+        const char* nB = nA + DSTAGE_BYTES;
+        const bool more = kt + 3 < nk, next = kt + 1 < nk;
+        const int st3 = (kt + 3) & 3;
+        SB();
+        // k step 0 of tile kt: MFMAs on (a0, b0); meanwhile fetch the k step 1 fragments and issue tile kt+3
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+#pragma unroll
+            for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[j], a0[i], acc[i][j], 0, 0, 0);
+            a1[i] = DA::frag(cA, wm + 32 * i, 1);
+            if (i < TN) b1[i] = DB::frag(cB, wn + 32 * i, 1);
+            if (more) dma_part(st3, i);
+            SB();
+        }
+        // k step 1: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+#pragma unroll
+            for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[j], a1[i], acc[i][j], 0, 0, 0);
+            if (next) { a0[i] = DA::frag(nA, wm + 32 * i, 0); if (i < TN) b0[i] = DB::frag(nB, wn + 32 * i, 0); }
+            SB();
+        }
+    }
+#undef SB
+
+    const int hf = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+        const int m = m0 + wm + 32 * i + (lane & 31);
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                const int n = n0 + wn + 32 * j + 8 * g + 4 * hf;
+                if (n >= N) continue;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] = acc[i][j][4 * g + e];
+                if (OUT_F32) {
+                    float* c = reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n;
+                    if (accumulate) {
+                        const float4 old = *reinterpret_cast<const float4*>(c);
+                        v[0] += old.x; v[1] += old.y; v[2] += old.z; v[3] += old.w;
+                    }
+                    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+                    if (R) {
+                        const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
+                        v[0] += lo_bf(rr.x); v[1] += hi_bf(rr.x); v[2] += lo_bf(rr.y); v[3] += hi_bf(rr.y);
+                    }
+                    uint2 o;
+                    o.x = pack_bf2(v[0], v[1]);
+                    o.y = pack_bf2(v[2], v[3]);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
+                }
+            }
+        }
+    }
+}
+
+template <int KIND, bool OUT_F32>
+static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
+    constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES;
+    static bool attr_set = false;
+    auto kern = k_gemm_dma<KIND, OUT_F32>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles = ((g.M + DTILE - 1) / DTILE) * ((g.N + DTILE - 1) / DTILE);
+    kern<<<tiles, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
+                                       (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate);
+    return hipGetLastError();
+}
+
 template <int KIND, bool OUT_F32>
 static hipError_t pick_tile(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
-    // 256x256 tiles when they fill the 256 CUs at least once, 128x128 otherwise
+    // 256x256 tiles when they can occupy most of the 256 CUs, 128x128 otherwise
     const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big >= 160) return launch<KIND, 256, 256, OUT_F32>(g, a_bytes, b_bytes, st);
+    if (big >= 160) return launch_dma<KIND, OUT_F32>(g, a_bytes, b_bytes, st);
     return launch<KIND, 128, 128, OUT_F32>(g, a_bytes, b_bytes, st);
 }
 
