@@ -26,39 +26,82 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
-// [64][D] bf16 tile, global -> LDS, rows tok0.. of a [*, ld] buffer at column col0
-template <int D, int PITCH>
-__device__ __forceinline__ void load_tile64(char* lds, __amdgpu_buffer_rsrc_t rs, uint32_t tok0, int ld, int col0) {
-    constexpr int CPR = D / 8;
-#pragma unroll
-    for (int i = 0; i < 64 * CPR / ATHREADS; i++) {
-        const int c = threadIdx.x + ATHREADS * i;
-        const int r = c / CPR, ch = c % CPR;
-        const uint32_t off = ((tok0 + r) * (uint32_t)ld + (uint32_t)(col0 + ch * 8)) * 2u;
-        const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
-        *reinterpret_cast<i32x4*>(lds + r * PITCH + ch * 16) = v;
+// A staged tile is 64 rows x D bf16, rows contiguous (D*2 bytes), 16-byte chunks XOR-swizzled by
+// the row so that both the row-wise ds_read_b128 fragments and the transposing
+// ds_read_b64_tr_b16 fragments avoid bank conflicts without padding -- which lets the tile be
+// filled by direct global->LDS loads (each wave instruction deposits 1 KB of consecutive LDS).
+template <int D>
+struct Tile {
+    static constexpr int ROWB = D * 2;             // bytes per row
+    static constexpr int BYTES = 64 * ROWB;
+    static constexpr int CPR = D / 8;              // 16-byte chunks per row
+    // XOR mask for the 16-byte chunk index of a row.  Rows r..r+15 must spread a fixed logical chunk over
+    // all bank groups (ds_read_b128 fragments), while four consecutive rows must land in four different
+    // 64-byte slots (the 4-row x 32-byte footprint of a ds_read_b64_tr_b16 lane block): both hold when the
+    // row bits are rotated so that the low two select the slot and the next ones the chunk inside it.
+    __device__ static __forceinline__ int swz(int row) {
+        if (D == 128) { const int x = row & 15; return ((x & 3) << 2) | (x >> 2); }
+        const int x = (row >> 1) & 7;
+        return ((x & 1) << 2) | (x >> 1);
     }
-}
 
-// rows rb + (lane%32), k = 16kk + 8(lane/32) .. +7 along d
-template <int PITCH>
-__device__ __forceinline__ bf16x8 frag_rows(const char* lds, int rb, int kk) {
-    const int l = threadIdx.x & 63;
-    return *reinterpret_cast<const bf16x8*>(lds + (rb + (l & 31)) * PITCH + (16 * kk + 8 * (l >> 5)) * 2);
-}
+    // Issue this wave's share of the tile whose first row is token tok0 (rows of ld elements, column col0).
+    // Rows past the buffer extent deposit zeros.
+    template <int NW = ATHREADS / WAVE>
+    __device__ static __forceinline__ void dma(uint32_t lds_tile, i32x4 rs, uint32_t tok0, int ld, int col0) {
+        constexpr int PER_WAVE = BYTES / 1024 / NW;   // DMA instructions per wave
+        const int w = threadIdx.x >> 6, L = threadIdx.x & 63;
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; i++) {
+            const int q = w * PER_WAVE + i;                 // 1 KB block of the tile
+            const int row = q * (1024 / ROWB) + L / CPR;
+            const int logical = (L % CPR) ^ swz(row);
+            const uint32_t voff = ((tok0 + row) * (uint32_t)ld + (uint32_t)(col0 + logical * 8)) * 2u;
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + q * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(dst), "v"(voff), "s"(rs) : "memory");
+        }
+    }
+    // Per-lane byte offsets of the fragment reads, computed once per kernel: the swizzle depends only
+    // on the lane, so inside the loops every LDS address is (stage base + table entry + constant).
+    struct Offsets {
+        int rows[D / 16];        // frag_rows: k step kk, row block at 0
+        int cols0[D / 32];       // frag_cols: channel block dt, k step 0, first 4 rows
+        int cols1[D / 32];       //            ... rows +8
+    };
+    __device__ static __forceinline__ Offsets offsets() {
+        Offsets o;
+        const int l = threadIdx.x & 63;
+        const int r = l & 31;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; kk++) o.rows[kk] = r * ROWB + (((2 * kk + (l >> 5)) ^ swz(r)) << 4);
+        const int row = 4 * (l >> 5) + ((l & 15) >> 2);
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) {
+            const int col = 32 * dt + 16 * ((l >> 4) & 1) + 4 * (l & 3);
+            const int c = col >> 3, within = (col & 7) * 2;
+            o.cols0[dt] = row * ROWB + ((c ^ swz(row)) << 4) + within;
+            o.cols1[dt] = (row + 8) * ROWB + ((c ^ swz(row + 8)) << 4) + within;
+        }
+        return o;
+    }
+    // rows 32*rblk + (lane%32), k = 16kk + 8(lane/32) .. +7 along d
+    __device__ static __forceinline__ bf16x8 frag_rows(const char* t, const Offsets& o, int rblk, int kk) {
+        return *reinterpret_cast<const bf16x8*>(t + rblk * 32 * ROWB + o.rows[kk]);
+    }
+    // transposed fragment: result row = tile column 32*dt + (lane%32); the lane's 8 k values are tile
+    // rows 16kk + 8j + 4(lane/32) + e  (j = 0,1; e = 0..3)
+    __device__ static __forceinline__ bf16x8 frag_cols(const char* t, const Offsets& o, int dt, int kk) {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(t + kk * 16 * ROWB + o.cols0[dt]));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(t + kk * 16 * ROWB + o.cols1[dt]));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+};
 
-// transposed fragment: result row = tile column cb + (lane%32); the lane's 8 k values are
-// tile rows 16kk + 8j + 4(lane/32) + e  (j = 0,1; e = 0..3)
-template <int PITCH>
-__device__ __forceinline__ bf16x8 frag_cols(const char* lds, int cb, int kk) {
-    const int l = threadIdx.x & 63;
-    const int row = 16 * kk + 4 * (l >> 5) + ((l & 15) >> 2);
-    const int col = cb + 16 * ((l >> 4) & 1) + 4 * (l & 3);
-    const char* p = lds + row * PITCH + col * 2;
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 8 * PITCH));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+__device__ __forceinline__ i32x4 make_rsrc_words(const void* base, uint32_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    return i32x4{(int)(uint32_t)p, (int)(uint32_t)(p >> 32), (int)bytes, 0x00020000};
 }
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // accumulator registers 8*half .. 8*half+7 -> bf16 operand
 __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int half) {
@@ -66,6 +109,28 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int half) {
 #pragma unroll
     for (int i = 0; i < 4; i++) r.u[i] = pack_bf2(a[8 * half + 2 * i], a[8 * half + 2 * i + 1]);
     return r.v;
+}
+
+// Software-pipelined MFMA sequence: NGROUPS groups of G (fragment load, MFMA) pairs; the fragments of
+// group g+1 are requested from LDS before the MFMAs of group g are issued, and a scheduling fence
+// after every group keeps the compiler from re-serialising load -> wait -> MFMA.
+template <int NGROUPS, int G, typename L, typename M>
+__device__ __forceinline__ void mfma_pipeline(L load, M mma) {
+    bf16x8 cur[G], nxt[G];
+#pragma unroll
+    for (int i = 0; i < G; i++) cur[i] = load(i);
+#pragma unroll
+    for (int g = 0; g < NGROUPS; g++) {
+        if (g + 1 < NGROUPS) {
+#pragma unroll
+            for (int i = 0; i < G; i++) nxt[i] = load((g + 1) * G + i);
+        }
+#pragma unroll
+        for (int i = 0; i < G; i++) mma(g * G + i, cur[i]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < G; i++) cur[i] = nxt[i];
+    }
 }
 
 template <int D>
@@ -82,11 +147,11 @@ __device__ __forceinline__ void load_qfrag(bf16x8 (&f)[D / 16], __amdgpu_buffer_
 
 // ------------------------------------------------------------------ forward
 template <int D>
-__global__ __launch_bounds__(ATHREADS) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+__global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                        bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh) {
-    constexpr int PK = D * 2 + 16, PV = D * 2 + 64;
-    __shared__ __attribute__((aligned(16))) char sK[64 * PK];
-    __shared__ __attribute__((aligned(16))) char sV[64 * PV];
+    using TL = Tile<D>;
+    constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
+    extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
@@ -94,6 +159,14 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_fwd(const bf16_t* __restrict_
     const int query = q0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
+    const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const typename TL::Offsets offs = TL::offsets();
+    auto issue = [&](int st, int kv) {
+        TL::dma(lds0 + st * STAGE, rsw, tokb + kv, ld, A + h * D);
+        TL::dma(lds0 + st * STAGE + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+    };
+    issue(0, 0);
 
     bf16x8 qf[D / 16];
     load_qfrag<D>(qf, rs, tokb + query, ld, h * D);
@@ -107,60 +180,75 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_fwd(const bf16_t* __restrict_
     const float c = LOG2E / sqrtf((float)D);
 
     const int q_last = min(qb * 128 + 127, S - 1);
-    for (int kv0 = 0; kv0 <= q_last; kv0 += 64) {
-        __syncthreads();
-        load_tile64<D, PK>(sK, rs, tokb + kv0, ld, A + h * D);
-        load_tile64<D, PV>(sV, rs, tokb + kv0, ld, 2 * A + h * D);
-        __syncthreads();
+    int t = 0;
+    for (int kv0 = 0; kv0 <= q_last; kv0 += 64, t++) {
+        wait_dma();
+        __syncthreads();   // tile t is in LDS for everyone; everyone has finished with tile t-1
+        if (kv0 + 64 <= q_last) issue((t + 1) & 1, kv0 + 64);
+        const char* sK = smem + (t & 1) * STAGE;
+        const char* sV = sK + TL::BYTES;
         if (kv0 > q0 + 31) continue;  // every key of the tile lies after every query of this wave
         f32x16 sacc[2];
 #pragma unroll
-        for (int tl = 0; tl < 2; tl++) {
+        for (int tl = 0; tl < 2; tl++)
 #pragma unroll
             for (int r = 0; r < 16; r++) sacc[tl][r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < D / 16; kk++)
-                sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<PK>(sK, 32 * tl, kk), qf[kk], sacc[tl], 0, 0, 0);
-        }
+        // S^T = K Q^T: index -> (key half tl, k step kk)
+        mfma_pipeline<2 * (D / 16) / 4, 4>(
+            [&](int idx) { return TL::frag_rows(sK, offs, idx / (D / 16), idx % (D / 16)); },
+            [&](int idx, bf16x8 f) {
+                const int tl = idx / (D / 16), kk = idx % (D / 16);
+                sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], sacc[tl], 0, 0, 0);
+            });
+        // raw scores; m and the exponent live in the log2 domain of the scaled scores: p = 2^(s*c - m)
         float tmax = -INFINITY;
-        const bool diag = kv0 + 63 > q0;
+        if (kv0 + 63 > q0) {   // tile touches the diagonal: drop keys after the query
+#pragma unroll
+            for (int tl = 0; tl < 2; tl++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int key = kv0 + 32 * tl + 8 * (r >> 2) + 4 * hf + (r & 3);
+                    if (key > query) sacc[tl][r] = -INFINITY;
+                }
+        }
 #pragma unroll
         for (int tl = 0; tl < 2; tl++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                float s = sacc[tl][r] * c;
-                if (diag) {
-                    const int key = kv0 + 32 * tl + 8 * (r >> 2) + 4 * hf + (r & 3);
-                    if (key > query) s = -INFINITY;
-                }
-                sacc[tl][r] = s;
-                tmax = fmaxf(tmax, s);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, WAVE));
-        const float mn = fmaxf(m, tmax);
-        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+            for (int r = 0; r < 16; r++) tmax = fmaxf(tmax, sacc[tl][r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, WAVE)) * c;
+        // The running reference m only moves when some query's tile maximum exceeds it by more than
+        // 2^8: probabilities then stay below 256 (exact in fp32, representable in bf16) and the
+        // rescale of the output accumulators is skipped for almost every tile.
+        if (__any(tmax > m + 8.0f)) {
+            const float mn = fmaxf(m, tmax);
+            const float alpha = __builtin_amdgcn_exp2f(m - mn);
+            lsum *= alpha;
+            m = mn;
+#pragma unroll
+            for (int i = 0; i < D / 32; i++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) oacc[i][r] *= alpha;
+        }
         float psum = 0.f;
 #pragma unroll
         for (int tl = 0; tl < 2; tl++)
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const float p = __builtin_amdgcn_exp2f(sacc[tl][r] - mn);
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[tl][r], c, -m));
                 sacc[tl][r] = p;
                 psum += p;
             }
-        lsum = lsum * alpha + psum;
-        m = mn;
+        lsum += psum;
+        bf16x8 pf[4];
 #pragma unroll
-        for (int i = 0; i < D / 32; i++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) oacc[i][r] *= alpha;
-#pragma unroll
-        for (int kk = 0; kk < 4; kk++) {
-            const bf16x8 pf = pack8(sacc[kk >> 1], kk & 1);
-#pragma unroll
-            for (int dt = 0; dt < D / 32; dt++)
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<PV>(sV, 32 * dt, kk), pf, oacc[dt], 0, 0, 0);
-        }
+        for (int kk = 0; kk < 4; kk++) pf[kk] = pack8(sacc[kk >> 1], kk & 1);
+        // O^T += V^T P^T: index -> (key step kk, channel block dt)
+        mfma_pipeline<4 * (D / 32) / 4, 4>(
+            [&](int idx) { return TL::frag_cols(sV, offs, idx % (D / 32), idx / (D / 32)); },
+            [&](int idx, bf16x8 f) {
+                const int kk = idx / (D / 32), dt = idx % (D / 32);
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[kk], oacc[dt], 0, 0, 0);
+            });
     }
     lsum += __shfl_xor(lsum, 32, WAVE);
     if (query < S) {
@@ -204,13 +292,13 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_delta(const bf16_t* __restric
 
 // --------------------------------------------------------------- backward: dQ
 template <int D>
-__global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+__global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                           const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                           const float* __restrict__ lse, const float* __restrict__ dvec,
                                                           bf16_t* __restrict__ dqkv, int S, int nh) {
-    constexpr int PK = D * 2 + 16, PV = D * 2 + 16;
-    __shared__ __attribute__((aligned(16))) char sK[64 * PK];
-    __shared__ __attribute__((aligned(16))) char sV[64 * PV];
+    using TL = Tile<D>;
+    constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
+    extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
     const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
@@ -219,6 +307,14 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dq(const bf16_t* __restri
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
     const __amdgpu_buffer_rsrc_t rsdo = make_rsrc(dout, do_bytes);
+    const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const typename TL::Offsets offs = TL::offsets();
+    auto issue = [&](int st, int kv) {
+        TL::dma(lds0 + st * STAGE, rsw, tokb + kv, ld, A + h * D);
+        TL::dma(lds0 + st * STAGE + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+    };
+    issue(0, 0);
 
     bf16x8 qf[D / 16], dof[D / 16];
     load_qfrag<D>(qf, rs, tokb + query, ld, h * D);
@@ -237,23 +333,27 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dq(const bf16_t* __restri
         for (int r = 0; r < 16; r++) dq[i][r] = 0.f;
 
     const int q_last = min(qb * 128 + 127, S - 1);
-    for (int kv0 = 0; kv0 <= q_last; kv0 += 64) {
-        __syncthreads();
-        load_tile64<D, PK>(sK, rs, tokb + kv0, ld, A + h * D);
-        load_tile64<D, PV>(sV, rs, tokb + kv0, ld, 2 * A + h * D);
-        __syncthreads();
+    int t = 0;
+    for (int kv0 = 0; kv0 <= q_last; kv0 += 64, t++) {
+        wait_dma();
+        __syncthreads();   // tile t is in LDS for everyone; everyone has finished with tile t-1
+        if (kv0 + 64 <= q_last) issue((t + 1) & 1, kv0 + 64);
+        const char* sK = smem + (t & 1) * STAGE;
+        const char* sV = sK + TL::BYTES;
         if (kv0 > q0 + 31) continue;
         f32x16 sacc[2], pacc[2];
 #pragma unroll
-        for (int tl = 0; tl < 2; tl++) {
+        for (int tl = 0; tl < 2; tl++)
 #pragma unroll
             for (int r = 0; r < 16; r++) { sacc[tl][r] = 0.f; pacc[tl][r] = 0.f; }
-#pragma unroll
-            for (int kk = 0; kk < D / 16; kk++) {
-                sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<PK>(sK, 32 * tl, kk), qf[kk], sacc[tl], 0, 0, 0);
-                pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<PV>(sV, 32 * tl, kk), dof[kk], pacc[tl], 0, 0, 0);
-            }
-        }
+        // S^T = K Q^T and dP^T = V dO^T: index -> (k step kk, {K half 0, K half 1, V half 0, V half 1})
+        mfma_pipeline<D / 16, 4>(
+            [&](int idx) { return TL::frag_rows((idx & 2) ? sV : sK, offs, idx & 1, idx >> 2); },
+            [&](int idx, bf16x8 f) {
+                const int kk = idx >> 2, tl = idx & 1;
+                if (idx & 2) pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dof[kk], pacc[tl], 0, 0, 0);
+                else sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], sacc[tl], 0, 0, 0);
+            });
         const bool diag = kv0 + 63 > q0;
 #pragma unroll
         for (int tl = 0; tl < 2; tl++)
@@ -266,13 +366,16 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dq(const bf16_t* __restri
                 }
                 sacc[tl][r] = p * (pacc[tl][r] - dl);  // dS^T (before the 1/sqrt(d) factor)
             }
+        bf16x8 sf[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; kk++) {
-            const bf16x8 sf = pack8(sacc[kk >> 1], kk & 1);
-#pragma unroll
-            for (int dt = 0; dt < D / 32; dt++)
-                dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<PK>(sK, 32 * dt, kk), sf, dq[dt], 0, 0, 0);
-        }
+        for (int kk = 0; kk < 4; kk++) sf[kk] = pack8(sacc[kk >> 1], kk & 1);
+        // dQ^T += K^T dS^T: index -> (key step kk, channel block dt)
+        mfma_pipeline<4 * (D / 32) / 4, 4>(
+            [&](int idx) { return TL::frag_cols(sK, offs, idx % (D / 32), idx / (D / 32)); },
+            [&](int idx, bf16x8 f) {
+                const int kk = idx / (D / 32), dt = idx % (D / 32);
+                dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk], dq[dt], 0, 0, 0);
+            });
     }
     if (query < S) {
         bf16_t* row = dqkv + (size_t)(tokb + query) * ld + h * D;
@@ -289,28 +392,56 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dq(const bf16_t* __restri
 }
 
 // ----------------------------------------------------------- backward: dK, dV
+// 8 waves: wave = (query half qh, key group kw).  A workgroup owns 128 keys (4 groups of 32) and walks
+// the query tiles from its diagonal to the end; of every 64-query tile a wave takes the 32 queries of
+// its half, so two waves per SIMD overlap each other's MFMA and softmax phases.  The two halves' dK, dV
+// sums are added through LDS at the end (fixed order: deterministic).
+constexpr int KVTHREADS = 512;
 template <int D>
-__global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
-                                                           const bf16_t* __restrict__ dout, uint32_t do_bytes,
-                                                           const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                           bf16_t* __restrict__ dqkv, int S, int nh) {
-    constexpr int PQ = D * 2 + 16;
-    __shared__ __attribute__((aligned(16))) char sQ[64 * PQ];
-    __shared__ __attribute__((aligned(16))) char sO[64 * PQ];
-    __shared__ __attribute__((aligned(16))) float sL[64];
-    __shared__ __attribute__((aligned(16))) float sD[64];
+__global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+                                                            const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                            const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                            bf16_t* __restrict__ dqkv, int S, int nh) {
+    using TL = Tile<D>;
+    constexpr int NW = KVTHREADS / WAVE;
+    constexpr int STAGE = 2 * TL::BYTES;                              // Q tile | dO tile
+    // LDS: two Q|dO stages, the workgroup's K (2 tiles) and V (2 tiles), then lse/delta[2][64|64]
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const char* sKV = smem + 2 * STAGE;
+    float* sLD = reinterpret_cast<float*>(smem + 2 * STAGE + 4 * TL::BYTES);
     const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
-    const int k0 = kb * 128 + wave * 32;
+    const int kw = wave & 3, qh = wave >> 2;
+    const int k0 = kb * 128 + kw * 32;
     const int key = k0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
-    const __amdgpu_buffer_rsrc_t rsdo = make_rsrc(dout, do_bytes);
-
-    bf16x8 kf[D / 16], vf[D / 16];
-    load_qfrag<D>(kf, rs, tokb + key, ld, A + h * D);
-    load_qfrag<D>(vf, rs, tokb + key, ld, 2 * A + h * D);
+    const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
+    const i32x4 rswdo = make_rsrc_words(dout, do_bytes);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const typename TL::Offsets offs = TL::offsets();
+    auto issue = [&](int st, int q) {
+        TL::template dma<NW>(lds0 + st * STAGE, rsw, tokb + q, ld, h * D);
+        TL::template dma<NW>(lds0 + st * STAGE + TL::BYTES, rswdo, tokb + q, A, h * D);
+    };
+    // lse (log2 domain) and delta of the 64 queries starting at q: thread i < 64 -> lse, 64 <= i < 128 -> delta
+    auto stat = [&](int q) -> float {
+        const int i = threadIdx.x & 63, qq = q + i;
+        if (threadIdx.x >= 128 || qq >= S) return 0.f;
+        const size_t at = ((size_t)b * nh + h) * S + qq;
+        return threadIdx.x < 64 ? lse[at] * LOG2E : dvec[at];
+    };
+    // K, V of keys kb*128 .. +127: resident for the whole kernel (first wait_dma below covers them)
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+        TL::template dma<NW>(lds0 + 2 * STAGE + i * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + h * D);
+        TL::template dma<NW>(lds0 + 2 * STAGE + (2 + i) * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, 2 * A + h * D);
+    }
+    issue(0, kb * 128);
+    float nstat = stat(kb * 128);
+    const char* sKw = sKV + (kw >> 1) * TL::BYTES;        // tile holding this wave's 32 keys (row block kw & 1)
+    const char* sVw = sKw + 2 * TL::BYTES;
     const float sc = 1.0f / sqrtf((float)D);
     const float c = LOG2E * sc;
     f32x16 dk[D / 32], dv[D / 32];
@@ -319,91 +450,156 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_bwd_dkv(const bf16_t* __restr
 #pragma unroll
         for (int r = 0; r < 16; r++) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-    for (int qt = kb * 128; qt < S; qt += 64) {
-        __syncthreads();
-        load_tile64<D, PQ>(sQ, rs, tokb + qt, ld, h * D);
-        load_tile64<D, PQ>(sO, rsdo, tokb + qt, A, h * D);
-        if (threadIdx.x < 64) {
-            const int q = qt + threadIdx.x;
-            const bool ok = q < S;
-            sL[threadIdx.x] = ok ? lse[((size_t)b * nh + h) * S + q] * LOG2E : 0.f;
-            sD[threadIdx.x] = ok ? dvec[((size_t)b * nh + h) * S + q] : 0.f;
+    int t = 0;
+    for (int qt = kb * 128; qt < S; qt += 64, t++) {
+        if (threadIdx.x < 128) sLD[(t & 1) * 128 + threadIdx.x] = nstat;   // lse / delta of tile t (fetched a step ago)
+        wait_dma();
+        __syncthreads();   // tile t and its lse/delta are in LDS for everyone; everyone has finished with tile t-1
+        if (qt + 64 < S) { issue((t + 1) & 1, qt + 64); nstat = stat(qt + 64); }
+        const char* sQ = smem + (t & 1) * STAGE;
+        const char* sO = sQ + TL::BYTES;
+        const float* sL = sLD + (t & 1) * 128;
+        const float* sD = sL + 64;
+        const int q0 = qt + 32 * qh;                 // this wave's 32 queries of the tile
+        if (q0 + 31 < k0) continue;                  // all of them precede every key of this wave
+        f32x16 sacc, pacc;
+#pragma unroll
+        for (int r = 0; r < 16; r++) { sacc[r] = 0.f; pacc[r] = 0.f; }
+        // S = Q K^T and dP = dO V^T.  Fragment stream: per k step kk the four fragments Q, K, dO, V;
+        // an MFMA is issued when its second operand arrives (odd index).
+        {
+            bf16x8 first;
+            mfma_pipeline<4 * (D / 16) / 4, 4>(
+                [&](int idx) {
+                    const int kk = idx >> 2, w = idx & 3;
+                    return w == 0 ? TL::frag_rows(sQ, offs, qh, kk) : w == 1 ? TL::frag_rows(sKw, offs, kw & 1, kk)
+                         : w == 2 ? TL::frag_rows(sO, offs, qh, kk) : TL::frag_rows(sVw, offs, kw & 1, kk);
+                },
+                [&](int idx, bf16x8 f) {
+                    const int w = idx & 3;
+                    if (w == 0 || w == 2) first = f;
+                    else if (w == 1) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, sacc, 0, 0, 0);
+                    else pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, pacc, 0, 0, 0);
+                });
         }
-        __syncthreads();
-        if (qt + 63 < k0) continue;  // every query of the tile precedes every key of this wave
-        f32x16 sacc[2], pacc[2];
+        const bool edge = (q0 < k0 + 31) || (q0 + 31 >= S);
 #pragma unroll
-        for (int tl = 0; tl < 2; tl++) {
+        for (int g = 0; g < 4; g++) {
+            const int qi = 32 * qh + 8 * g + 4 * hf;
+            const float4 l4 = *reinterpret_cast<const float4*>(&sL[qi]);
+            const float4 d4 = *reinterpret_cast<const float4*>(&sD[qi]);
+            const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-            for (int r = 0; r < 16; r++) { sacc[tl][r] = 0.f; pacc[tl][r] = 0.f; }
-#pragma unroll
-            for (int kk = 0; kk < D / 16; kk++) {
-                sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<PQ>(sQ, 32 * tl, kk), kf[kk], sacc[tl], 0, 0, 0);
-                pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<PQ>(sO, 32 * tl, kk), vf[kk], pacc[tl], 0, 0, 0);
-            }
-        }
-        const bool edge = (qt < k0 + 31) || (qt + 63 >= S);
-#pragma unroll
-        for (int tl = 0; tl < 2; tl++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int qi = 32 * tl + 8 * g + 4 * hf;
-                const float4 l4 = *reinterpret_cast<const float4*>(&sL[qi]);
-                const float4 d4 = *reinterpret_cast<const float4*>(&sD[qi]);
-                const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const int r = 4 * g + e;
-                    float p = __builtin_amdgcn_exp2f(sacc[tl][r] * c - ls[e]);
-                    if (edge) {
-                        const int q = qt + qi + e;
-                        if (key > q || q >= S) p = 0.f;
-                    }
-                    sacc[tl][r] = p;
-                    pacc[tl][r] = p * (pacc[tl][r] - ds[e]);
+            for (int e = 0; e < 4; e++) {
+                const int r = 4 * g + e;
+                float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c, -ls[e]));
+                if (edge) {
+                    const int q = qt + qi + e;
+                    if (key > q || q >= S) p = 0.f;
                 }
-            }
-#pragma unroll
-        for (int kk = 0; kk < 4; kk++) {
-            const bf16x8 pf = pack8(sacc[kk >> 1], kk & 1);
-            const bf16x8 sf = pack8(pacc[kk >> 1], kk & 1);
-#pragma unroll
-            for (int dt = 0; dt < D / 32; dt++) {
-                dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<PQ>(sO, 32 * dt, kk), pf, dv[dt], 0, 0, 0);
-                dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<PQ>(sQ, 32 * dt, kk), sf, dk[dt], 0, 0, 0);
+                sacc[r] = p;
+                pacc[r] = p * (pacc[r] - ds[e]);
             }
         }
+        bf16x8 pf[2], sf[2];
+#pragma unroll
+        for (int kk = 0; kk < 2; kk++) { pf[kk] = pack8(sacc, kk); sf[kk] = pack8(pacc, kk); }
+        // dV^T += dO^T P and dK^T += Q^T dS over this wave's 32 queries (k steps 2qh, 2qh+1 of the tile):
+        // index -> (query step, channel block dt, {dO, Q})
+        mfma_pipeline<2 * (D / 32) * 2 / 4, 4>(
+            [&](int idx) { return TL::frag_cols((idx & 1) ? sQ : sO, offs, (idx >> 1) % (D / 32), 2 * qh + (idx >> 1) / (D / 32)); },
+            [&](int idx, bf16x8 f) {
+                const int dt = (idx >> 1) % (D / 32), kk = (idx >> 1) / (D / 32);
+                if (idx & 1) dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk], dk[dt], 0, 0, 0);
+                else dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[kk], dv[dt], 0, 0, 0);
+            });
     }
-    if (key < S) {
+    // add the second query half's sums to the first's: [kw][register][lane] floats in the stage memory
+    float* red = reinterpret_cast<float*>(smem);
+    constexpr int R = (D / 32) * 16;
+    __syncthreads();
+    if (qh == 1) {
+#pragma unroll
+        for (int i = 0; i < D / 32; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) red[(kw * R + i * 16 + r) * 64 + lane] = dk[i][r];
+    }
+    __syncthreads();
+    if (qh == 0) {
+#pragma unroll
+        for (int i = 0; i < D / 32; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) dk[i][r] += red[(kw * R + i * 16 + r) * 64 + lane];
+    }
+    __syncthreads();
+    if (qh == 1) {
+#pragma unroll
+        for (int i = 0; i < D / 32; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) red[(kw * R + i * 16 + r) * 64 + lane] = dv[i][r];
+    }
+    __syncthreads();
+    if (qh == 0 && key < S) {
         bf16_t* krow = dqkv + (size_t)(tokb + key) * ld + A + h * D;
         bf16_t* vrow = krow + A;
 #pragma unroll
         for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
             for (int g = 0; g < 4; g++) {
+                float w[4];
+#pragma unroll
+                for (int e = 0; e < 4; e++) w[e] = dv[dt][4 * g + e] + red[(kw * R + dt * 16 + 4 * g + e) * 64 + lane];
                 uint2 v;
                 v.x = pack_bf2(dk[dt][4 * g] * sc, dk[dt][4 * g + 1] * sc);
                 v.y = pack_bf2(dk[dt][4 * g + 2] * sc, dk[dt][4 * g + 3] * sc);
                 *reinterpret_cast<uint2*>(krow + 32 * dt + 8 * g + 4 * hf) = v;
-                v.x = pack_bf2(dv[dt][4 * g], dv[dt][4 * g + 1]);
-                v.y = pack_bf2(dv[dt][4 * g + 2], dv[dt][4 * g + 3]);
+                v.x = pack_bf2(w[0], w[1]);
+                v.y = pack_bf2(w[2], w[3]);
                 *reinterpret_cast<uint2*>(vrow + 32 * dt + 8 * g + 4 * hf) = v;
             }
     }
 }
 
 // ---------------------------------------------------------------- launchers
+template <typename K>
+static hipError_t set_lds(K kern, int bytes) {
+    return bytes > 48 * 1024 ? hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) : hipSuccess;
+}
+
+template <int D>
+static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float* lse, int B, int S, int nh, hipStream_t st) {
+    constexpr int LDS = 4 * Tile<D>::BYTES;
+    hipError_t e = set_lds(k_attn_fwd<D>, LDS);
+    if (e != hipSuccess) return e;
+    dim3 grid((S + 127) / 128, nh, B);
+    k_attn_fwd<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, const void* dout, uint32_t do_bytes,
+                        const float* lse, float* dvec, void* dqkv, int B, int S, int nh, hipStream_t st) {
+    constexpr int LDS = 4 * Tile<D>::BYTES, LDS_KV = 8 * Tile<D>::BYTES + 1024;
+    hipError_t e = set_lds(k_attn_bwd_dq<D>, LDS);
+    if (e != hipSuccess) return e;
+    e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
+    if (e != hipSuccess) return e;
+    dim3 grid((S + 127) / 128, nh, B);
+    const long rows = (long)B * S * nh;
+    k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
+    k_attn_bwd_dq<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+                                                  (bf16_t*)dqkv, S, nh);
+    k_attn_bwd_dkv<D><<<grid, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+                                                      (bf16_t*)dqkv, S, nh);
+    return hipGetLastError();
+}
+
 hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st) {
     const long bytes = (long)B * S * ld * 2;
     if (bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
-    dim3 grid((S + 127) / 128, nh, B);
-    if (d == 128)
-        k_attn_fwd<128><<<grid, ATHREADS, 0, st>>>((const bf16_t*)qkv, ld, (uint32_t)bytes, (bf16_t*)o, lse, S, nh);
-    else if (d == 64)
-        k_attn_fwd<64><<<grid, ATHREADS, 0, st>>>((const bf16_t*)qkv, ld, (uint32_t)bytes, (bf16_t*)o, lse, S, nh);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (d == 128) return fwd_d<128>(qkv, ld, (uint32_t)bytes, o, lse, B, S, nh, st);
+    if (d == 64) return fwd_d<64>(qkv, ld, (uint32_t)bytes, o, lse, B, S, nh, st);
+    return hipErrorInvalidValue;
 }
 
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
@@ -411,25 +607,9 @@ hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dou
     const long bytes = (long)B * S * ld * 2;
     const long do_bytes = (long)B * S * nh * d * 2;
     if (bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
-    dim3 grid((S + 127) / 128, nh, B);
-    const long rows = (long)B * S * nh;
-    const unsigned nb = (unsigned)((rows + 3) / 4);
-    if (d == 128) {
-        k_attn_delta<128><<<nb, ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
-        k_attn_bwd_dq<128><<<grid, ATHREADS, 0, st>>>((const bf16_t*)qkv, ld, (uint32_t)bytes, (const bf16_t*)dout,
-                                                      (uint32_t)do_bytes, lse, dvec, (bf16_t*)dqkv, S, nh);
-        k_attn_bwd_dkv<128><<<grid, ATHREADS, 0, st>>>((const bf16_t*)qkv, ld, (uint32_t)bytes, (const bf16_t*)dout,
-                                                       (uint32_t)do_bytes, lse, dvec, (bf16_t*)dqkv, S, nh);
-    } else if (d == 64) {
-        k_attn_delta<64><<<nb, ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
-        k_attn_bwd_dq<64><<<grid, ATHREADS, 0, st>>>((const bf16_t*)qkv, ld, (uint32_t)bytes, (const bf16_t*)dout,
-                                                     (uint32_t)do_bytes, lse, dvec, (bf16_t*)dqkv, S, nh);
-        k_attn_bwd_dkv<64><<<grid, ATHREADS, 0, st>>>((const bf16_t*)qkv, ld, (uint32_t)bytes, (const bf16_t*)dout,
-                                                      (uint32_t)do_bytes, lse, dvec, (bf16_t*)dqkv, S, nh);
-    } else {
-        return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, st);
+    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace hh
