@@ -96,9 +96,8 @@ struct TileLoader {
 // Workgroup -> tile mapping.  Consecutive workgroup ids land on different XCDs
 // (8 of them, each with its own L2), so ids are first regrouped per XCD and each
 // XCD then walks a compact block of tiles, GROUP_M tile rows at a time.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+__device__ __forceinline__ void tile_of_index(int id, int tiles_m, int tiles_n, int& tm, int& tn) {
     const int nb = tiles_m * tiles_n;
-    int id = blockIdx.x;
     const int per = nb >> 3;
     if (id < per * 8) id = (id & 7) * per + (id >> 3);
     constexpr int GROUP_M = 8;
@@ -127,7 +126,7 @@ __global__ __launch_bounds__(GTHREADS) void k_gemm_bf16(const bf16_t* __restrict
     char* const sB0 = smem + 2 * A_BYTES;
 
     int tm, tn;
-    tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
+    tile_of_index(blockIdx.x, (M + BM - 1) / BM, (N + BN - 1) / BN, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
@@ -291,7 +290,10 @@ template <int KIND, bool OUT_F32>
 __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, int lda, uint32_t a_bytes,
                                                        const bf16_t* __restrict__ B, int ldb, uint32_t b_bytes,
                                                        void* __restrict__ Cv, int ldc, const bf16_t* R, int ldr,
-                                                       int M, int N, int K, int accumulate) {
+                                                       int M, int N, int K, int accumulate,
+                                                       int block0, int ksplit, float* __restrict__ partial) {
+    // Workgroup blockIdx.x computes tile (block0 + blockIdx.x / ksplit) over the (blockIdx.x % ksplit)-th
+    // share of the k range.  With ksplit > 1 the fp32 sums go to partial[blockIdx.x][256][256] instead of C.
     constexpr bool A_KC = (KIND != GEMM_TN);
     constexpr bool B_KC = (KIND == GEMM_NT);
     using DA = DmaTile<A_KC>;
@@ -300,18 +302,22 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     extern __shared__ __attribute__((aligned(1024))) char smem[];   // [stage][A 16 KB | B 16 KB]
 
     int tm, tn;
-    tile_of_block((M + DTILE - 1) / DTILE, (N + DTILE - 1) / DTILE, tm, tn);
+    const int chunk = ksplit > 1 ? (int)blockIdx.x % ksplit : 0;
+    tile_of_index(block0 + (ksplit > 1 ? (int)blockIdx.x / ksplit : (int)blockIdx.x), (M + DTILE - 1) / DTILE,
+                  (N + DTILE - 1) / DTILE, tm, tn);
     const int m0 = tm * DTILE, n0 = tn * DTILE;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
+    const int nk_all = (K + DK - 1) / DK;
+    const int kbeg = (int)((long)chunk * nk_all / ksplit), kend = (int)((long)(chunk + 1) * nk_all / ksplit);
 
     const uint64_t pa = (uint64_t)A, pb = (uint64_t)B;
     const i32x4 rsA = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)a_bytes, 0x00020000};
     const i32x4 rsB = {(int)(uint32_t)pb, (int)(uint32_t)(pb >> 32), (int)b_bytes, 0x00020000};
     uint32_t voA[2], voB[2];
-#pragma unroll
-    for (int i = 0; i < 2; i++) { voA[i] = DA::voff(i, m0, lda); voB[i] = DB::voff(i, n0, ldb); }
     const uint32_t stepA = DA::kstep_bytes(lda), stepB = DB::kstep_bytes(ldb);
+#pragma unroll
+    for (int i = 0; i < 2; i++) { voA[i] = DA::voff(i, m0, lda) + kbeg * stepA; voB[i] = DB::voff(i, n0, ldb) + kbeg * stepB; }
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * 2048);
 
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-    const int nk = (K + DK - 1) / DK;
+    const int nk = kend - kbeg;
 #define SB() __builtin_amdgcn_sched_barrier(0)
     // one DMA instruction of the k tile being issued (i < 4: A part i, else B part i-4) into stage st
     auto dma_part = [&](int st, int i) {
@@ -382,6 +388,18 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
 #undef SB
 
     const int hf = lane >> 5;
+    if (ksplit > 1) {
+        float* pt = partial + (size_t)blockIdx.x * (DTILE * DTILE);
+#pragma unroll
+        for (int i = 0; i < TM; i++)
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+#pragma unroll
+                for (int g = 0; g < 4; g++)
+                    *reinterpret_cast<float4*>(pt + (wm + 32 * i + (lane & 31)) * DTILE + wn + 32 * j + 8 * g + 4 * hf) =
+                        make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; i++) {
         const int m = m0 + wm + 32 * i + (lane & 31);
@@ -417,6 +435,49 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     }
 }
 
+// Sums the ksplit fp32 partial tiles of each split tile in a fixed order and applies the epilogue.
+// 64 workgroups per tile; a thread owns 4 consecutive columns of one row.
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__ partial, int ksplit, int block0,
+                                                       void* __restrict__ Cv, int ldc, const bf16_t* R, int ldr,
+                                                       int M, int N, int accumulate) {
+    const int r = blockIdx.x >> 6, sub = blockIdx.x & 63;
+    int tm, tn;
+    tile_of_index(block0 + r, (M + DTILE - 1) / DTILE, (N + DTILE - 1) / DTILE, tm, tn);
+    const int q = sub * 256 + threadIdx.x;
+    const int row = q >> 6, col = (q & 63) * 4;
+    const float* p = partial + (size_t)r * ksplit * (DTILE * DTILE) + row * DTILE + col;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < ksplit; c++) {
+        const float4 t = *reinterpret_cast<const float4*>(p + (size_t)c * (DTILE * DTILE));
+        v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+    }
+    const int m = tm * DTILE + row, n = tn * DTILE + col;
+    if (m >= M || n >= N) return;
+    if (OUT_F32) {
+        float* c = reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n;
+        if (accumulate) {
+            const float4 old = *reinterpret_cast<const float4*>(c);
+            v[0] += old.x; v[1] += old.y; v[2] += old.z; v[3] += old.w;
+        }
+        *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        if (R) {
+            const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
+            v[0] += lo_bf(rr.x); v[1] += hi_bf(rr.x); v[2] += lo_bf(rr.y); v[3] += hi_bf(rr.y);
+        }
+        uint2 o;
+        o.x = pack_bf2(v[0], v[1]);
+        o.y = pack_bf2(v[2], v[3]);
+        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
+    }
+}
+
+constexpr int NUM_CU = 256;
+
+// Full rounds of 256 tiles run one tile per workgroup.  A last, partial round of R tiles would leave
+// most CUs idle, so it is cut along k into floor(256 / R) shares per tile (fp32 partials in `ws`,
+// summed in a fixed order by a small second kernel).
 template <int KIND, bool OUT_F32>
 static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
     constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES;
@@ -428,16 +489,32 @@ static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_byt
         attr_set = true;
     }
     const int tiles = ((g.M + DTILE - 1) / DTILE) * ((g.N + DTILE - 1) / DTILE);
-    kern<<<tiles, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
-                                       (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate);
+    const int nk = (g.K + DK - 1) / DK;
+    int full = tiles, tail = 0, ksplit = 1;
+    const int rem = tiles % NUM_CU;
+    if (rem > 0 && rem <= NUM_CU / 2 && g.ws) {
+        int s = NUM_CU / rem;
+        if (s > 8) s = 8;
+        while (s > 1 && (nk / s < 8 || (size_t)rem * s * DTILE * DTILE * sizeof(float) > g.ws_bytes)) s--;
+        if (s > 1) { full = tiles - rem; tail = rem; ksplit = s; }
+    }
+    if (full > 0)
+        kern<<<full, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
+                                     (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate, 0, 1, nullptr);
+    if (tail > 0) {
+        kern<<<tail * ksplit, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
+                                              (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate, full, ksplit, (float*)g.ws);
+        k_splitk_reduce<OUT_F32><<<tail * 64, 256, 0, st>>>((const float*)g.ws, ksplit, full, g.C, g.ldc, (const bf16_t*)g.R,
+                                                            g.ldr, g.M, g.N, g.accumulate);
+    }
     return hipGetLastError();
 }
 
 template <int KIND, bool OUT_F32>
 static hipError_t pick_tile(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
-    // 256x256 tiles when they can occupy most of the 256 CUs, 128x128 otherwise
+    // 256x256 tiles (k-split when they are few) unless the problem is small; 128x128 tiles otherwise
     const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big >= 160) return launch_dma<KIND, OUT_F32>(g, a_bytes, b_bytes, st);
+    if (big >= 64) return launch_dma<KIND, OUT_F32>(g, a_bytes, b_bytes, st);
     return launch<KIND, 128, 128, OUT_F32>(g, a_bytes, b_bytes, st);
 }
 

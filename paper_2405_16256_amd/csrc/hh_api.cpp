@@ -75,6 +75,7 @@ struct hh_ctx {
     std::vector<TraceRec> trace;  // events created by hh_trace_begin
     size_t trace_used;
     bool trace_on;
+    void* gemm_ws;                // k-split scratch inside the caller's workspace, set by each hot call
 };
 
 extern "C" int hh_ctx_create(hh_ctx** out, int device) {
@@ -84,7 +85,7 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess) return hip_fail(e, "hipGetDeviceCount");
     if (device < 0 || device >= n) return fail(HH_ERR_DEVICE, "hh_ctx_create: no HIP device %d (%d visible)", device, n);
-    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false};
+    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false, nullptr};
     if (!c) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out of host memory");
     *out = c;
     return HH_OK;
@@ -184,7 +185,7 @@ static SavedLayout saved_layout(const Dims& d) {
 }
 
 struct WorkLayout {
-    size_t m, dgu, dhn, dh, da, dqkv, dvec, partial, total;
+    size_t m, dgu, dhn, dh, da, dqkv, dvec, partial, gemm_ws, total;
 };
 static WorkLayout work_layout(const Dims& d) {
     WorkLayout w;
@@ -199,6 +200,7 @@ static WorkLayout work_layout(const Dims& d) {
     w.dqkv = take(T * 3 * d.A * d.es);
     w.dvec = take((size_t)d.B * d.nh * d.S * 4);
     w.partial = take((size_t)rmsnorm_bwd_blocks(d.T) * d.H * 4);
+    w.gemm_ws = take(d.dt == DT_BF16 ? GEMM_WS_BYTES : 0);
     w.total = off;
     return w;
 }
@@ -287,8 +289,9 @@ struct Traced {
     } while (0)
 static double attn_flop(const Dims& d) { return 4.0 * d.d * d.B * d.nh * ((double)d.S * (d.S + 1) / 2); }
 static double gemm_flop(const GemmDesc& g) { return 2.0 * g.M * g.N * g.K; }
-static hipError_t tgemm(hh_ctx* ctx, int dt, const GemmDesc& g, hipStream_t st) {
+static hipError_t tgemm(hh_ctx* ctx, int dt, GemmDesc g, hipStream_t st) {
     Traced t(ctx, st, g.kind, gemm_flop(g));
+    g.ws = ctx->gemm_ws; g.ws_bytes = ctx->gemm_ws ? GEMM_WS_BYTES : 0;
     return gemm(dt, g, st);
 }
 
@@ -332,7 +335,7 @@ static GemmDesc desc(int kind, int M, int N, int K, const void* A, int lda, cons
                      const void* R = nullptr, int ldr = 0, int out_f32 = 0, int acc = 0) {
     GemmDesc g;
     g.kind = kind; g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
-    g.R = R; g.ldr = ldr; g.out_f32 = out_f32; g.accumulate = acc;
+    g.R = R; g.ldr = ldr; g.out_f32 = out_f32; g.accumulate = acc; g.ws = nullptr; g.ws_bytes = 0;
     return g;
 }
 
@@ -346,6 +349,7 @@ static int layer_fwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     void* hn = at(saved, sl.hn); void* gu = at(saved, sl.gu);
     float* lse = (float*)at(saved, sl.lse); float* r1 = (float*)at(saved, sl.r1); float* r2 = (float*)at(saved, sl.r2);
     void* m = at(ws, wl.m);
+    ctx->gemm_ws = d.dt == DT_BF16 ? at(ws, wl.gemm_ws) : nullptr;
 
     TR(HH_TRACE_ELEMENTWISE, 2.0 * T * H * es, rmsnorm_fwd(dt, x, w->g_attn, xn, r1, T, H, cfg->rms_eps, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
@@ -410,6 +414,7 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     float* dvec = (float*)at(ws, wl.dvec); float* partial = (float*)at(ws, wl.partial);
     const int nblk = rmsnorm_bwd_blocks(T);
     acc = acc ? 1 : 0;
+    ctx->gemm_ws = d.dt == DT_BF16 ? at(ws, wl.gemm_ws) : nullptr;
 
     // MLP branch: y = h + m Wd^T
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, F, H, dy, H, w->w_down, F, m, F), st));                 // dm (in the m buffer)

@@ -24,7 +24,10 @@ struct GemmDesc {
     const void* R; int ldr;  // optional residual in the storage dtype, added before rounding (NULL: none)
     int out_f32;             // 1: C is fp32 regardless of the storage dtype (parameter gradients)
     int accumulate;          // 1: C += result
+    void* ws;                // optional scratch for k-split partial sums (bf16 path), may be NULL
+    size_t ws_bytes;
 };
+constexpr size_t GEMM_WS_BYTES = (size_t)64 << 20;   // enough for 256 partial tiles of 256x256 fp32
 hipError_t gemm(int dtype, const GemmDesc& g, hipStream_t st);
 
 // xn = x * r * g, r = 1/sqrt(mean(x^2)+eps) per row.
