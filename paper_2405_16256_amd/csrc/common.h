@@ -37,21 +37,23 @@ __device__ __forceinline__ float hi_bf(uint32_t p) { return __uint_as_float(p & 
 template <typename T> struct Vec;
 template <> struct Vec<float> {
     static constexpr int N = 4;
-    __device__ static __forceinline__ void load(const float* p, float* f) {
-        float4 v = *reinterpret_cast<const float4*>(p);
-        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-    }
+    typedef float4 Raw;
+    __device__ static __forceinline__ Raw raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    __device__ static __forceinline__ void widen(const Raw& v, float* f) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+    __device__ static __forceinline__ void load(const float* p, float* f) { widen(raw(p), f); }
     __device__ static __forceinline__ void store(float* p, const float* f) {
         *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
     }
 };
 template <> struct Vec<bf16_t> {
     static constexpr int N = 8;
-    __device__ static __forceinline__ void load(const bf16_t* p, float* f) {
-        uint4 v = *reinterpret_cast<const uint4*>(p);
+    typedef uint4 Raw;
+    __device__ static __forceinline__ Raw raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    __device__ static __forceinline__ void widen(const Raw& v, float* f) {
         f[0] = lo_bf(v.x); f[1] = hi_bf(v.x); f[2] = lo_bf(v.y); f[3] = hi_bf(v.y);
         f[4] = lo_bf(v.z); f[5] = hi_bf(v.z); f[6] = lo_bf(v.w); f[7] = hi_bf(v.w);
     }
+    __device__ static __forceinline__ void load(const bf16_t* p, float* f) { widen(raw(p), f); }
     __device__ static __forceinline__ void store(bf16_t* p, const float* f) {
         uint4 v;
         v.x = pack_bf2(f[0], f[1]); v.y = pack_bf2(f[2], f[3]);

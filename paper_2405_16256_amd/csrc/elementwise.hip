@@ -11,29 +11,65 @@ constexpr int TPB = 256;
 constexpr int NWAVES = TPB / WAVE;
 
 // ------------------------------------------------------------------ RMSNorm
+// A row of up to RC * TPB * V elements stays in registers between the reduction pass and the
+// output pass (RC raw 16-byte vectors per thread); longer rows are re-read (from L2).
+constexpr int RC = 6;
+
 template <typename T>
 __global__ __launch_bounds__(TPB) void k_rmsnorm_fwd(const T* __restrict__ x, const T* __restrict__ g,
                                                      T* __restrict__ xn, float* __restrict__ r, int H, float eps) {
     constexpr int V = Vec<T>::N;
+    typedef typename Vec<T>::Raw Raw;
     __shared__ float red[NWAVES];
     const size_t base = (size_t)blockIdx.x * H;
+    const bool cached = H <= RC * TPB * V;
+    Raw keep[RC];
     float ss = 0.f;
-    for (int c = threadIdx.x * V; c < H; c += TPB * V) {
-        float f[V];
-        Vec<T>::load(x + base + c, f);
+    if (cached) {
 #pragma unroll
-        for (int e = 0; e < V; e++) ss += f[e] * f[e];
+        for (int i = 0; i < RC; i++) {
+            const int c = (threadIdx.x + i * TPB) * V;
+            if (c < H) {
+                keep[i] = Vec<T>::raw(x + base + c);
+                float f[V];
+                Vec<T>::widen(keep[i], f);
+#pragma unroll
+                for (int e = 0; e < V; e++) ss += f[e] * f[e];
+            }
+        }
+    } else {
+        for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+            float f[V];
+            Vec<T>::load(x + base + c, f);
+#pragma unroll
+            for (int e = 0; e < V; e++) ss += f[e] * f[e];
+        }
     }
     ss = block_sum<NWAVES>(ss, red);
     const float rs = 1.0f / sqrtf(ss / (float)H + eps);
     if (threadIdx.x == 0) r[blockIdx.x] = rs;
-    for (int c = threadIdx.x * V; c < H; c += TPB * V) {
-        float f[V], gg[V];
-        Vec<T>::load(x + base + c, f);
-        Vec<T>::load(g + c, gg);
+    if (cached) {
 #pragma unroll
-        for (int e = 0; e < V; e++) f[e] = f[e] * rs * gg[e];
-        Vec<T>::store(xn + base + c, f);
+        for (int i = 0; i < RC; i++) {
+            const int c = (threadIdx.x + i * TPB) * V;
+            if (c < H) {
+                float f[V], gg[V];
+                Vec<T>::widen(keep[i], f);
+                Vec<T>::load(g + c, gg);
+#pragma unroll
+                for (int e = 0; e < V; e++) f[e] = f[e] * rs * gg[e];
+                Vec<T>::store(xn + base + c, f);
+            }
+        }
+    } else {
+        for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+            float f[V], gg[V];
+            Vec<T>::load(x + base + c, f);
+            Vec<T>::load(g + c, gg);
+#pragma unroll
+            for (int e = 0; e < V; e++) f[e] = f[e] * rs * gg[e];
+            Vec<T>::store(xn + base + c, f);
+        }
     }
 }
 
@@ -45,6 +81,7 @@ __global__ __launch_bounds__(TPB) void k_rmsnorm_bwd(const T* __restrict__ dxn, 
                                                      const T* __restrict__ dres, T* __restrict__ dx,
                                                      float* __restrict__ partial, int T_rows, int H, int rpb) {
     constexpr int V = Vec<T>::N;
+    typedef typename Vec<T>::Raw Raw;
     extern __shared__ float colacc[];  // [H]
     __shared__ float red[NWAVES];
     for (int c = threadIdx.x * V; c < H; c += TPB * V)
@@ -53,32 +90,70 @@ __global__ __launch_bounds__(TPB) void k_rmsnorm_bwd(const T* __restrict__ dxn, 
     const int row0 = blockIdx.x * rpb;
     const int row1 = min(T_rows, row0 + rpb);
     const float invH = 1.0f / (float)H;
+    const bool cached = H <= RC * TPB * V;
     for (int row = row0; row < row1; row++) {
         const size_t base = (size_t)row * H;
         const float rs = r[row];
         float s = 0.f;
-        for (int c = threadIdx.x * V; c < H; c += TPB * V) {
-            float d[V], xx[V], gg[V];
-            Vec<T>::load(dxn + base + c, d);
-            Vec<T>::load(x + base + c, xx);
-            Vec<T>::load(g + c, gg);
+        if (cached) {
+            Raw kd[RC], kx[RC];
 #pragma unroll
-            for (int e = 0; e < V; e++) s += d[e] * gg[e] * xx[e];
-        }
-        const float c1 = block_sum<NWAVES>(s, red) * rs * invH;  // mean_j(w_j u_j)
-        for (int c = threadIdx.x * V; c < H; c += TPB * V) {
-            float d[V], xx[V], gg[V], rr[V], o[V];
-            Vec<T>::load(dxn + base + c, d);
-            Vec<T>::load(x + base + c, xx);
-            Vec<T>::load(g + c, gg);
-            Vec<T>::load(dres + base + c, rr);
+            for (int i = 0; i < RC; i++) {
+                const int c = (threadIdx.x + i * TPB) * V;
+                if (c < H) {
+                    kd[i] = Vec<T>::raw(dxn + base + c);
+                    kx[i] = Vec<T>::raw(x + base + c);
+                    float d[V], xx[V], gg[V];
+                    Vec<T>::widen(kd[i], d);
+                    Vec<T>::widen(kx[i], xx);
+                    Vec<T>::load(g + c, gg);
 #pragma unroll
-            for (int e = 0; e < V; e++) {
-                const float u = xx[e] * rs;
-                colacc[c + e] += d[e] * u;
-                o[e] = rr[e] + rs * (d[e] * gg[e] - u * c1);
+                    for (int e = 0; e < V; e++) s += d[e] * gg[e] * xx[e];
+                }
             }
-            Vec<T>::store(dx + base + c, o);
+            const float c1 = block_sum<NWAVES>(s, red) * rs * invH;  // mean_j(w_j u_j)
+#pragma unroll
+            for (int i = 0; i < RC; i++) {
+                const int c = (threadIdx.x + i * TPB) * V;
+                if (c < H) {
+                    float d[V], xx[V], gg[V], rr[V], o[V];
+                    Vec<T>::widen(kd[i], d);
+                    Vec<T>::widen(kx[i], xx);
+                    Vec<T>::load(g + c, gg);
+                    Vec<T>::load(dres + base + c, rr);
+#pragma unroll
+                    for (int e = 0; e < V; e++) {
+                        const float u = xx[e] * rs;
+                        colacc[c + e] += d[e] * u;
+                        o[e] = rr[e] + rs * (d[e] * gg[e] - u * c1);
+                    }
+                    Vec<T>::store(dx + base + c, o);
+                }
+            }
+        } else {
+            for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+                float d[V], xx[V], gg[V];
+                Vec<T>::load(dxn + base + c, d);
+                Vec<T>::load(x + base + c, xx);
+                Vec<T>::load(g + c, gg);
+#pragma unroll
+                for (int e = 0; e < V; e++) s += d[e] * gg[e] * xx[e];
+            }
+            const float c1 = block_sum<NWAVES>(s, red) * rs * invH;
+            for (int c = threadIdx.x * V; c < H; c += TPB * V) {
+                float d[V], xx[V], gg[V], rr[V], o[V];
+                Vec<T>::load(dxn + base + c, d);
+                Vec<T>::load(x + base + c, xx);
+                Vec<T>::load(g + c, gg);
+                Vec<T>::load(dres + base + c, rr);
+#pragma unroll
+                for (int e = 0; e < V; e++) {
+                    const float u = xx[e] * rs;
+                    colacc[c + e] += d[e] * u;
+                    o[e] = rr[e] + rs * (d[e] * gg[e] - u * c1);
+                }
+                Vec<T>::store(dx + base + c, o);
+            }
         }
     }
     float* out = partial + (size_t)blockIdx.x * H;
@@ -87,20 +162,31 @@ __global__ __launch_bounds__(TPB) void k_rmsnorm_bwd(const T* __restrict__ dxn, 
         for (int e = 0; e < V; e++) out[c + e] = colacc[c + e];
 }
 
-// out[j] (=|+=) sum_b partial[b][j].  64 columns x 4 row groups per workgroup.
+// out[j] (=|+=) sum_b partial[b][j].  A workgroup covers 256 columns (one float4 per thread column
+// group) with 4 row groups that are combined through LDS in a fixed order.
 __global__ __launch_bounds__(TPB) void k_colsum_reduce(const float* __restrict__ partial, int nblk, int H,
                                                        float* __restrict__ out, int accumulate) {
-    __shared__ float red[NWAVES][WAVE];
+    __shared__ float4 red[NWAVES][WAVE];
     const int cx = threadIdx.x % WAVE, ry = threadIdx.x / WAVE;
-    const int col = blockIdx.x * WAVE + cx;
-    float s = 0.f;
-    if (col < H)
-        for (int b = ry; b < nblk; b += NWAVES) s += partial[(size_t)b * H + col];
+    const int col = (blockIdx.x * WAVE + cx) * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col < H) {
+        const float* p = partial + col;
+#pragma unroll 8
+        for (int b = ry; b < nblk; b += NWAVES) {
+            const float4 v = *reinterpret_cast<const float4*>(p + (size_t)b * H);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+    }
     red[ry][cx] = s;
     __syncthreads();
     if (ry == 0 && col < H) {
-        float t = red[0][cx] + red[1][cx] + red[2][cx] + red[3][cx];
-        out[col] = accumulate ? out[col] + t : t;
+        float4 t = red[0][cx];
+#pragma unroll
+        for (int i = 1; i < NWAVES; i++) { t.x += red[i][cx].x; t.y += red[i][cx].y; t.z += red[i][cx].z; t.w += red[i][cx].w; }
+        float4* o = reinterpret_cast<float4*>(out + col);
+        if (accumulate) { const float4 old = *o; t.x += old.x; t.y += old.y; t.z += old.z; t.w += old.w; }
+        *o = t;
     }
 }
 
@@ -225,7 +311,7 @@ hipError_t rmsnorm_bwd(int dtype, const void* dxn, const void* x, const float* r
 }
 
 hipError_t colsum_reduce(const float* partial, int nblk, int H, float* out, int accumulate, hipStream_t st) {
-    k_colsum_reduce<<<(H + WAVE - 1) / WAVE, TPB, 0, st>>>(partial, nblk, H, out, accumulate);
+    k_colsum_reduce<<<(H + 4 * WAVE - 1) / (4 * WAVE), TPB, 0, st>>>(partial, nblk, H, out, accumulate);
     return hipGetLastError();
 }
 
