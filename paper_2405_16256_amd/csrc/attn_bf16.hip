@@ -189,16 +189,13 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restri
         const char* sV = sK + TL::BYTES;
         if (kv0 > q0 + 31) continue;  // every key of the tile lies after every query of this wave
         f32x16 sacc[2];
-#pragma unroll
-        for (int tl = 0; tl < 2; tl++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) sacc[tl][r] = 0.f;
-        // S^T = K Q^T: index -> (key half tl, k step kk)
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // S^T = K Q^T: index -> (key half tl, k step kk); the first k step starts from a zero accumulator
         mfma_pipeline<2 * (D / 16) / 4, 4>(
             [&](int idx) { return TL::frag_rows(sK, offs, idx / (D / 16), idx % (D / 16)); },
             [&](int idx, bf16x8 f) {
                 const int tl = idx / (D / 16), kk = idx % (D / 16);
-                sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], sacc[tl], 0, 0, 0);
+                sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], kk ? sacc[tl] : zero16, 0, 0, 0);
             });
         // raw scores; m and the exponent live in the log2 domain of the scaled scores: p = 2^(s*c - m)
         float tmax = -INFINITY;
@@ -342,17 +339,14 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __res
         const char* sV = sK + TL::BYTES;
         if (kv0 > q0 + 31) continue;
         f32x16 sacc[2], pacc[2];
-#pragma unroll
-        for (int tl = 0; tl < 2; tl++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) { sacc[tl][r] = 0.f; pacc[tl][r] = 0.f; }
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         // S^T = K Q^T and dP^T = V dO^T: index -> (k step kk, {K half 0, K half 1, V half 0, V half 1})
         mfma_pipeline<D / 16, 4>(
             [&](int idx) { return TL::frag_rows((idx & 2) ? sV : sK, offs, idx & 1, idx >> 2); },
             [&](int idx, bf16x8 f) {
                 const int kk = idx >> 2, tl = idx & 1;
-                if (idx & 2) pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dof[kk], pacc[tl], 0, 0, 0);
-                else sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], sacc[tl], 0, 0, 0);
+                if (idx & 2) pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dof[kk], kk ? pacc[tl] : zero16, 0, 0, 0);
+                else sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], kk ? sacc[tl] : zero16, 0, 0, 0);
             });
         const bool diag = kv0 + 63 > q0;
 #pragma unroll
@@ -401,7 +395,7 @@ template <int D>
 __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                             const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                             const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                            bf16_t* __restrict__ dqkv, int S, int nh) {
+                                                            bf16_t* __restrict__ dqkv, int S, int nh, int B) {
     using TL = Tile<D>;
     constexpr int NW = KVTHREADS / WAVE;
     constexpr int STAGE = 2 * TL::BYTES;                              // Q tile | dO tile
@@ -409,7 +403,10 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const char* sKV = smem + 2 * STAGE;
     float* sLD = reinterpret_cast<float*>(smem + 2 * STAGE + 4 * TL::BYTES);
-    const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // flattened grid: key block first (block 0 has the most query tiles), so the long jobs of every
+    // head and sample are dispatched before the short ones
+    const int nhb = nh * B;
+    const int kb = blockIdx.x / nhb, h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int kw = wave & 3, qh = wave >> 2;
@@ -463,8 +460,7 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
         const int q0 = qt + 32 * qh;                 // this wave's 32 queries of the tile
         if (q0 + 31 < k0) continue;                  // all of them precede every key of this wave
         f32x16 sacc, pacc;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { sacc[r] = 0.f; pacc[r] = 0.f; }
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         // S = Q K^T and dP = dO V^T.  Fragment stream: per k step kk the four fragments Q, K, dO, V;
         // an MFMA is issued when its second operand arrives (odd index).
         {
@@ -476,10 +472,10 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
                          : w == 2 ? TL::frag_rows(sO, offs, qh, kk) : TL::frag_rows(sVw, offs, kw & 1, kk);
                 },
                 [&](int idx, bf16x8 f) {
-                    const int w = idx & 3;
+                    const int w = idx & 3, kk = idx >> 2;
                     if (w == 0 || w == 2) first = f;
-                    else if (w == 1) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, sacc, 0, 0, 0);
-                    else pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, pacc, 0, 0, 0);
+                    else if (w == 1) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, kk ? sacc : zero16, 0, 0, 0);
+                    else pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, kk ? pacc : zero16, 0, 0, 0);
                 });
         }
         const bool edge = (q0 < k0 + 31) || (q0 + 31 >= S);
@@ -589,8 +585,8 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
     k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
     k_attn_bwd_dq<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
                                                   (bf16_t*)dqkv, S, nh);
-    k_attn_bwd_dkv<D><<<grid, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                      (bf16_t*)dqkv, S, nh);
+    k_attn_bwd_dkv<D><<<dim3(grid.x * nh * B), KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
+                                                                         dvec, (bf16_t*)dqkv, S, nh, B);
     return hipGetLastError();
 }
 
