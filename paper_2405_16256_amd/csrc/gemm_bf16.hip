@@ -288,12 +288,17 @@ struct DmaTile {
 
 template <int KIND, bool OUT_F32>
 __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, int lda, uint32_t a_bytes,
-                                                       const bf16_t* __restrict__ B, int ldb, uint32_t b_bytes,
-                                                       void* __restrict__ Cv, int ldc, const bf16_t* R, int ldr,
-                                                       int M, int N, int K, int accumulate,
-                                                       int block0, int ksplit, float* __restrict__ partial) {
-    // Workgroup blockIdx.x computes tile (block0 + blockIdx.x / ksplit) over the (blockIdx.x % ksplit)-th
-    // share of the k range.  With ksplit > 1 the fp32 sums go to partial[blockIdx.x][256][256] instead of C.
+                                                  const bf16_t* __restrict__ B, int ldb, uint32_t b_bytes,
+                                                  void* __restrict__ Cv, int ldc, const bf16_t* R, int ldr,
+                                                  int M, int N, int K, int accumulate,
+                                                  int block0, int block_end, int ksplit, float* __restrict__ partial) {
+    // ksplit == 1: the workgroup walks tiles block0 + blockIdx.x, + gridDim.x, ... < block_end over the whole
+    //   k range; the first DMA stages of the next tile are issued before the epilogue of the current one.
+    //   For fp32 "+=" outputs every second group of 8 workgroups cuts its FIRST tile into two k halves
+    //   (two read-modify-write epilogues): from then on its epilogues fall half a tile period after the
+    //   others', so the chip's 128 MB read+write bursts overlap the other half's MFMA phase.
+    // ksplit  > 1: workgroup blockIdx.x computes tile (block0 + blockIdx.x / ksplit) over the
+    //   (blockIdx.x % ksplit)-th share of the k range and writes fp32 sums to partial[blockIdx.x][256][256].
     constexpr bool A_KC = (KIND != GEMM_TN);
     constexpr bool B_KC = (KIND == GEMM_NT);
     using DA = DmaTile<A_KC>;
@@ -301,138 +306,204 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     constexpr int TM = 4, TN = 2;
     extern __shared__ __attribute__((aligned(1024))) char smem[];   // [stage][A 16 KB | B 16 KB]
 
-    int tm, tn;
+    const int tiles_m = (M + DTILE - 1) / DTILE, tiles_n = (N + DTILE - 1) / DTILE;
     const int chunk = ksplit > 1 ? (int)blockIdx.x % ksplit : 0;
-    tile_of_index(block0 + (ksplit > 1 ? (int)blockIdx.x / ksplit : (int)blockIdx.x), (M + DTILE - 1) / DTILE,
-                  (N + DTILE - 1) / DTILE, tm, tn);
-    const int m0 = tm * DTILE, n0 = tn * DTILE;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int stride = ksplit > 1 ? block_end : (int)gridDim.x;        // split workgroups own a single tile
+    int tix = block0 + (ksplit > 1 ? (int)blockIdx.x / ksplit : (int)blockIdx.x);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
     const int nk_all = (K + DK - 1) / DK;
-    const int kbeg = (int)((long)chunk * nk_all / ksplit), kend = (int)((long)(chunk + 1) * nk_all / ksplit);
+    int kbeg = (int)((long)chunk * nk_all / ksplit), kend = (int)((long)(chunk + 1) * nk_all / ksplit);
+    int nk = kend - kbeg;
+    int acc_now = accumulate;
+    // 0: whole tiles; 1: first half of the first tile is running; 2: its second half is running
+    int skew = (OUT_F32 && ksplit == 1 && ((blockIdx.x >> 3) & 1) && tix + (int)gridDim.x < block_end && nk_all >= 16) ? 1 : 0;
+    if (skew) { kend = nk_all / 2; nk = kend; }
 
     const uint64_t pa = (uint64_t)A, pb = (uint64_t)B;
     const i32x4 rsA = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)a_bytes, 0x00020000};
     const i32x4 rsB = {(int)(uint32_t)pb, (int)(uint32_t)(pb >> 32), (int)b_bytes, 0x00020000};
     uint32_t voA[2], voB[2];
     const uint32_t stepA = DA::kstep_bytes(lda), stepB = DB::kstep_bytes(ldb);
-#pragma unroll
-    for (int i = 0; i < 2; i++) { voA[i] = DA::voff(i, m0, lda) + kbeg * stepA; voB[i] = DB::voff(i, n0, ldb) + kbeg * stepB; }
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * 2048);
 
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
-
-    const int nk = kend - kbeg;
 #define SB() __builtin_amdgcn_sched_barrier(0)
-    // one DMA instruction of the k tile being issued (i < 4: A part i, else B part i-4) into stage st
+    // one DMA instruction of the k tile being issued (i < 2: A part i, else B part i-2) into stage st
     auto dma_part = [&](int st, int i) {
         const uint32_t base = wave_lds + st * (2 * DSTAGE_BYTES);
         if (i < 2) { dma16(base + i * 1024, voA[i], rsA); voA[i] += stepA; }
         else { dma16(base + DSTAGE_BYTES + (i - 2) * 1024, voB[i - 2], rsB); voB[i - 2] += stepB; }
     };
-    // prologue: tiles 0, 1, 2 on their way; tile 0 landed; its first fragments in registers
+    // point the DMA offsets at tile (m0, n0) and put its first three k tiles on their way
+    auto start_tile = [&](int m0, int n0) {
 #pragma unroll
-    for (int s = 0; s < DSTAGES - 1; s++)
-        if (s < nk) {
+        for (int i = 0; i < 2; i++) { voA[i] = DA::voff(i, m0, lda) + kbeg * stepA; voB[i] = DB::voff(i, n0, ldb) + kbeg * stepB; }
 #pragma unroll
-            for (int i = 0; i < 4; i++) dma_part(s, i);
-        }
-    if (nk > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else if (nk > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+        for (int s = 0; s < DSTAGES - 1; s++)
+            if (s < nk) {
 #pragma unroll
-    for (int i = 0; i < TM; i++) a0[i] = DA::frag(smem, wm + 32 * i, 0);
-#pragma unroll
-    for (int j = 0; j < TN; j++) b0[j] = DB::frag(smem + DSTAGE_BYTES, wn + 32 * j, 0);
+                for (int i = 0; i < 4; i++) dma_part(s, i);
+            }
+    };
 
-    for (int kt = 0; kt < nk; kt++) {
-        // tile kt+1 must have landed (it is read before the next barrier); only tile kt+2 may be outstanding
-        if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // tile kt+1 complete in LDS for everyone; everyone is done reading tile kt-1
-        const char* cA = smem + (kt & 3) * (2 * DSTAGE_BYTES);
-        const char* cB = cA + DSTAGE_BYTES;
-        const char* nA = smem + ((kt + 1) & 3) * (2 * DSTAGE_BYTES);
-        const char* nB = nA + DSTAGE_BYTES;
-        const bool more = kt + 3 < nk, next = kt + 1 < nk;
-        const int st3 = (kt + 3) & 3;
-        SB();
-        // k step 0 of tile kt: MFMAs on (a0, b0); meanwhile fetch the k step 1 fragments and issue tile kt+3
-#pragma unroll
-        for (int i = 0; i < TM; i++) {
-#pragma unroll
-            for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[j], a0[i], acc[i][j], 0, 0, 0);
-            a1[i] = DA::frag(cA, wm + 32 * i, 1);
-            if (i < TN) b1[i] = DB::frag(cB, wn + 32 * i, 1);
-            if (more) dma_part(st3, i);
-            SB();
-        }
-        // k step 1: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1
-#pragma unroll
-        for (int i = 0; i < TM; i++) {
-#pragma unroll
-            for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[j], a1[i], acc[i][j], 0, 0, 0);
-            if (next) { a0[i] = DA::frag(nA, wm + 32 * i, 0); if (i < TN) b0[i] = DB::frag(nB, wn + 32 * i, 0); }
-            SB();
-        }
-    }
-#undef SB
+    int tm, tn;
+    tile_of_index(tix, tiles_m, tiles_n, tm, tn);
+    int m0 = tm * DTILE, n0 = tn * DTILE;
+    start_tile(m0, n0);
+    bool fresh = true;   // no stores of an earlier tile are in flight behind the DMAs
 
-    const int hf = lane >> 5;
-    if (ksplit > 1) {
-        float* pt = partial + (size_t)blockIdx.x * (DTILE * DTILE);
+    for (;;) {
+        f32x16 acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; i++)
 #pragma unroll
             for (int j = 0; j < TN; j++)
 #pragma unroll
-                for (int g = 0; g < 4; g++)
-                    *reinterpret_cast<float4*>(pt + (wm + 32 * i + (lane & 31)) * DTILE + wn + 32 * j + 8 * g + 4 * hf) =
-                        make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-        return;
-    }
+                for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+        // k tile 0 landed.  After an epilogue its stores sit behind the DMAs in the memory queue, so the
+        // count-based wait only applies to a fresh start.
+        if (fresh && nk > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (fresh && nk > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
 #pragma unroll
-    for (int i = 0; i < TM; i++) {
-        const int m = m0 + wm + 32 * i + (lane & 31);
-        if (m >= M) continue;
+        for (int i = 0; i < TM; i++) a0[i] = DA::frag(smem, wm + 32 * i, 0);
 #pragma unroll
-        for (int j = 0; j < TN; j++) {
+        for (int j = 0; j < TN; j++) b0[j] = DB::frag(smem + DSTAGE_BYTES, wn + 32 * j, 0);
+
+        for (int kt = 0; kt < nk; kt++) {
+            // tile kt+1 must have landed (it is read before the next barrier); only tile kt+2 may be outstanding
+            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();   // tile kt+1 complete in LDS for everyone; everyone is done reading tile kt-1
+            const char* cA = smem + (kt & 3) * (2 * DSTAGE_BYTES);
+            const char* cB = cA + DSTAGE_BYTES;
+            const char* nA = smem + ((kt + 1) & 3) * (2 * DSTAGE_BYTES);
+            const char* nB = nA + DSTAGE_BYTES;
+            const bool more = kt + 3 < nk, next = kt + 1 < nk;
+            const int st3 = (kt + 3) & 3;
+            SB();
+            // k step 0 of tile kt: MFMAs on (a0, b0); meanwhile fetch the k step 1 fragments and issue tile kt+3
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-                const int n = n0 + wn + 32 * j + 8 * g + 4 * hf;
-                if (n >= N) continue;
-                float v[4];
+            for (int i = 0; i < TM; i++) {
 #pragma unroll
-                for (int e = 0; e < 4; e++) v[e] = acc[i][j][4 * g + e];
-                if (OUT_F32) {
-                    float* c = reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n;
-                    if (accumulate) {
-                        const float4 old = *reinterpret_cast<const float4*>(c);
-                        v[0] += old.x; v[1] += old.y; v[2] += old.z; v[3] += old.w;
-                    }
-                    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
-                } else {
-                    if (R) {
-                        const uint2 rr = *reinterpret_cast<const uint2*>(R + (size_t)m * ldr + n);
-                        v[0] += lo_bf(rr.x); v[1] += hi_bf(rr.x); v[2] += lo_bf(rr.y); v[3] += hi_bf(rr.y);
-                    }
-                    uint2 o;
-                    o.x = pack_bf2(v[0], v[1]);
-                    o.y = pack_bf2(v[2], v[3]);
-                    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
-                }
+                for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[j], a0[i], acc[i][j], 0, 0, 0);
+                a1[i] = DA::frag(cA, wm + 32 * i, 1);
+                if (i < TN) b1[i] = DB::frag(cB, wn + 32 * i, 1);
+                if (more) dma_part(st3, i);
+                SB();
+            }
+            // k step 1: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1
+#pragma unroll
+            for (int i = 0; i < TM; i++) {
+#pragma unroll
+                for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[j], a1[i], acc[i][j], 0, 0, 0);
+                if (next) { a0[i] = DA::frag(nA, wm + 32 * i, 0); if (i < TN) b0[i] = DB::frag(nB, wn + 32 * i, 0); }
+                SB();
             }
         }
+
+        if (ksplit > 1) {
+            float* pt = partial + (size_t)blockIdx.x * (DTILE * DTILE);
+#pragma unroll
+            for (int i = 0; i < TM; i++)
+#pragma unroll
+                for (int j = 0; j < TN; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++)
+                        *reinterpret_cast<float4*>(pt + (wm + 32 * i + (lane & 31)) * DTILE + wn + 32 * j + 8 * g + 4 * hf) =
+                            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            return;
+        }
+
+        // next piece of work of this workgroup: start its loads before writing this one out
+        const int cm0 = m0, cn0 = n0, cacc = acc_now;
+        bool has_next;
+        if (skew == 1) {          // same tile, second k half, added to what the first half wrote
+            skew = 2; kbeg = kend; kend = nk_all; nk = kend - kbeg; acc_now = 1; has_next = true;
+        } else {
+            if (skew == 2) { skew = 0; kbeg = 0; kend = nk_all; nk = nk_all; acc_now = accumulate; }
+            tix += stride;
+            has_next = tix < block_end;
+            if (has_next) { tile_of_index(tix, tiles_m, tiles_n, tm, tn); m0 = tm * DTILE; n0 = tn * DTILE; }
+        }
+        if (has_next) {
+            __syncthreads();   // every wave has finished reading the LDS stages
+            start_tile(m0, n0);
+            fresh = false;
+        }
+
+        // epilogue: lane owns row m = .. + (lane & 31); register 4g+e holds column n = .. + 8g + 4(lane>>5) + e.
+        // What has to be read (old fp32 sums, or the bf16 residual) is fetched for a whole row block in one
+        // batch of branch-free loads -- invalid lanes read the tile's first element -- before anything is stored.
+#pragma unroll
+        for (int i = 0; i < TM; i++) {
+            const int m = cm0 + wm + 32 * i + (lane & 31);
+            bool valid[TN][4];
+            int n_of[TN][4];
+#pragma unroll
+            for (int j = 0; j < TN; j++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    n_of[j][g] = cn0 + wn + 32 * j + 8 * g + 4 * hf;
+                    valid[j][g] = m < M && n_of[j][g] < N;
+                }
+            if (OUT_F32) {
+                float* Cf = reinterpret_cast<float*>(Cv);
+                float4 old[TN][4];
+                if (cacc) {
+#pragma unroll
+                    for (int j = 0; j < TN; j++)
+#pragma unroll
+                        for (int g = 0; g < 4; g++) {
+                            const size_t at = valid[j][g] ? (size_t)m * ldc + n_of[j][g] : (size_t)cm0 * ldc + cn0;
+                            old[j][g] = *reinterpret_cast<const float4*>(Cf + at);
+                        }
+                }
+#pragma unroll
+                for (int j = 0; j < TN; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                        if (cacc) { v.x += old[j][g].x; v.y += old[j][g].y; v.z += old[j][g].z; v.w += old[j][g].w; }
+                        if (valid[j][g]) *reinterpret_cast<float4*>(Cf + (size_t)m * ldc + n_of[j][g]) = v;
+                    }
+            } else {
+                bf16_t* Cb = reinterpret_cast<bf16_t*>(Cv);
+                uint2 res[TN][4];
+                if (R) {
+#pragma unroll
+                    for (int j = 0; j < TN; j++)
+#pragma unroll
+                        for (int g = 0; g < 4; g++) {
+                            const size_t at = valid[j][g] ? (size_t)m * ldr + n_of[j][g] : (size_t)cm0 * ldr + cn0;
+                            res[j][g] = *reinterpret_cast<const uint2*>(R + at);
+                        }
+                }
+#pragma unroll
+                for (int j = 0; j < TN; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) v[e] = acc[i][j][4 * g + e];
+                        if (R) {
+                            v[0] += lo_bf(res[j][g].x); v[1] += hi_bf(res[j][g].x);
+                            v[2] += lo_bf(res[j][g].y); v[3] += hi_bf(res[j][g].y);
+                        }
+                        uint2 o;
+                        o.x = pack_bf2(v[0], v[1]);
+                        o.y = pack_bf2(v[2], v[3]);
+                        if (valid[j][g]) *reinterpret_cast<uint2*>(Cb + (size_t)m * ldc + n_of[j][g]) = o;
+                    }
+            }
+        }
+        if (!has_next) return;
     }
+#undef SB
 }
 
 // Sums the ksplit fp32 partial tiles of each split tile in a fixed order and applies the epilogue.
@@ -498,12 +569,14 @@ static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_byt
         while (s > 1 && (nk / s < 8 || (size_t)rem * s * DTILE * DTILE * sizeof(float) > g.ws_bytes)) s--;
         if (s > 1) { full = tiles - rem; tail = rem; ksplit = s; }
     }
-    if (full > 0)
-        kern<<<full, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
-                                     (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate, 0, 1, nullptr);
+    if (full > 0)   // one workgroup per CU walks its share of the tiles
+        kern<<<full < NUM_CU ? full : NUM_CU, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes,
+                                                               g.C, g.ldc, (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate,
+                                                               0, full, 1, nullptr);
     if (tail > 0) {
         kern<<<tail * ksplit, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
-                                              (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate, full, ksplit, (float*)g.ws);
+                                              (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate, full, full + tail, ksplit,
+                                              (float*)g.ws);
         k_splitk_reduce<OUT_F32><<<tail * 64, 256, 0, st>>>((const float*)g.ws, ksplit, full, g.C, g.ldc, (const bf16_t*)g.R,
                                                             g.ldr, g.M, g.N, g.accumulate);
     }
