@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known HBM traffic) for scaling rocprofv3 byte counters")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % a.gpus,
@@ -81,6 +83,12 @@ def main():
         # steady-state training: gradients accumulate, nothing is zeroed inside the timed region
         hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
 
+    if a.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=L.DEV).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
