@@ -122,7 +122,7 @@ def main():
                    "model_flop_per_step": flop_step},
         "tokens_per_s": round(tokens_s, 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "k_gemm_bf16 (%s)" % dom, "bound": "mfma", "achieved": round(achieved, 1),
+        "roofline": {"kernel": "k_gemm_dma (%s, incl. its k-split tail launches)" % dom, "bound": "mfma", "achieved": round(achieved, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": None, "launches": launches, "avg_launch_ms": round(dms / launches, 4),
                      "flop_per_launch": dwork / launches},

@@ -7,10 +7,12 @@
 //
 // Two kernels, both on v_mfma_f32_32x32x16_bf16:
 //   * k_gemm_dma: 256x256 tile of C per workgroup of 8 waves (2 per SIMD, each a 128x64
-//     sub-tile), k advancing 32 at a time through four LDS stages that are filled straight
-//     from global memory (buffer_load ... lds), two tiles always in flight.  The loop is
-//     laid out by hand: MFMAs of one k step interleaved with the LDS fragment reads of the
-//     next and with the DMA issue of the tile three steps ahead.
+//     sub-tile), k advancing 64 at a time through two LDS stages that are filled straight
+//     from global memory (buffer_load ... lds), so a k-contiguous operand row is fetched as
+//     one whole 128-byte line per stage.  The loop is laid out by hand: MFMAs of one k step
+//     interleaved with the LDS fragment reads of the next, one barrier per stage placed
+//     before its last k step, after which the other stage's first fragments and the DMA of
+//     the stage after that are issued.
 //   * k_gemm_bf16: 128x128 tile per workgroup of 4 waves, register-staged double buffer,
 //     for problems too small to fill the chip with 256x256 tiles.
 //
@@ -232,14 +234,14 @@ static hipError_t launch(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, 
 
 
 // ---------------------------------------------------------------------------
-// Large-tile kernel: 256x256 tile of C, k advances 32 at a time through FOUR LDS
+// Large-tile kernel: 256x256 tile of C, k advances 64 at a time through TWO LDS
 // stages that are filled straight from global memory (buffer_load ... lds: no
-// VGPR staging, no ds_write).  Tiles k+1, k+2 are in flight while tile k feeds the
-// matrix cores and tile k+3 is issued, so one tile has three compute phases to land.
-constexpr int DK = 32;           // k per stage
-constexpr int DSTAGES = 4;
+// VGPR staging, no ds_write).  A k-contiguous operand row is 128 bytes per stage,
+// i.e. one full cache line per request.
+constexpr int DK = 64;           // k per stage
+constexpr int DSTAGES = 2;
 constexpr int DTILE = 256;
-constexpr int DSTAGE_BYTES = DTILE * DK * 2;   // one operand, one stage: 16 KB
+constexpr int DSTAGE_BYTES = DTILE * DK * 2;   // one operand, one stage: 32 KB
 
 __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, i32x4 rs) {
     // each lane moves 16 bytes from (rs.base + voff) to LDS byte (lds_addr + 16*lane); lanes past the
@@ -249,29 +251,29 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, i32x4 rs
 
 template <bool KC>
 struct DmaTile {
-    // Per wave and stage: 2 instructions of 1 KB (8 waves).  Instruction i of wave w covers
-    //   KC : rows 16*(2w+i) .. +15   (64 B per row, lane -> row L/4, physical chunk L%4)
+    // Per wave and stage: 4 instructions of 1 KB (8 waves).  Instruction i of wave w covers
+    //   KC : rows 8*(4w+i) .. +7     (128 B per row, lane -> row L/8, physical chunk L%8)
     //   KS : k rows 2*(4w+i), +1     (512 B per k row, lane -> k row L/32, physical chunk L%32)
     // The global address picks the logical chunk that the swizzle places at that physical slot.
     __device__ static __forceinline__ uint32_t voff(int i, int row0, int ld) {
         const int w = threadIdx.x >> 6, L = threadIdx.x & 63;
         if (KC) {
-            const int r = 16 * (2 * w + i) + (L >> 2);
-            const int logical = (L & 3) ^ ((r >> 2) & 3);
+            const int r = 8 * (4 * w + i) + (L >> 3);
+            const int logical = (L & 7) ^ ((r >> 1) & 7);
             return ((uint32_t)(row0 + r) * (uint32_t)ld + (uint32_t)(logical * 8)) * 2u;
         } else {
-            const int k = 2 * (2 * w + i) + (L >> 5);
+            const int k = 2 * (4 * w + i) + (L >> 5);
             const int lbyte = ((L & 31) * 16) ^ ((k & 3) << 6);
             return ((uint32_t)k * (uint32_t)ld + (uint32_t)row0) * 2u + (uint32_t)lbyte;
         }
     }
     __device__ static __forceinline__ uint32_t kstep_bytes(int ld) { return KC ? DK * 2u : (uint32_t)DK * (uint32_t)ld * 2u; }
-    // fragment of 32 rows starting at rb, k step kk (0,1)
+    // fragment of 32 rows starting at rb, k step kk (0..3)
     __device__ static __forceinline__ bf16x8 frag(const char* lds, int rb, int kk) {
         const int l = threadIdx.x & 63;
         if (KC) {
             const int r = rb + (l & 31), c = 2 * kk + (l >> 5);
-            return *reinterpret_cast<const bf16x8*>(lds + r * 64 + ((c ^ ((r >> 2) & 3)) << 4));
+            return *reinterpret_cast<const bf16x8*>(lds + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
         } else {
             typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
             const int col = rb + 16 * ((l >> 4) & 1) + 4 * (l & 3);
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     using DA = DmaTile<A_KC>;
     using DB = DmaTile<B_KC>;
     constexpr int TM = 4, TN = 2;
-    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [stage][A 16 KB | B 16 KB]
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // [stage][A 32 KB | B 32 KB]
 
     const int tiles_m = (M + DTILE - 1) / DTILE, tiles_n = (N + DTILE - 1) / DTILE;
     const int chunk = ksplit > 1 ? (int)blockIdx.x % ksplit : 0;
@@ -317,33 +319,33 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     int nk = kend - kbeg;
     int acc_now = accumulate;
     // 0: whole tiles; 1: first half of the first tile is running; 2: its second half is running
-    int skew = (OUT_F32 && ksplit == 1 && ((blockIdx.x >> 3) & 1) && tix + (int)gridDim.x < block_end && nk_all >= 16) ? 1 : 0;
+    int skew = (OUT_F32 && ksplit == 1 && ((blockIdx.x >> 3) & 1) && tix + (int)gridDim.x < block_end && nk_all >= 8) ? 1 : 0;
     if (skew) { kend = nk_all / 2; nk = kend; }
 
     const uint64_t pa = (uint64_t)A, pb = (uint64_t)B;
     const i32x4 rsA = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)a_bytes, 0x00020000};
     const i32x4 rsB = {(int)(uint32_t)pb, (int)(uint32_t)(pb >> 32), (int)b_bytes, 0x00020000};
-    uint32_t voA[2], voB[2];
+    uint32_t voA[4], voB[4];
     const uint32_t stepA = DA::kstep_bytes(lda), stepB = DB::kstep_bytes(ldb);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
-    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * 2048);
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * 4096);
 
 #define SB() __builtin_amdgcn_sched_barrier(0)
-    // one DMA instruction of the k tile being issued (i < 2: A part i, else B part i-2) into stage st
+    // one DMA instruction of the k tile being issued (i < 4: A part i, else B part i-4) into stage st
     auto dma_part = [&](int st, int i) {
         const uint32_t base = wave_lds + st * (2 * DSTAGE_BYTES);
-        if (i < 2) { dma16(base + i * 1024, voA[i], rsA); voA[i] += stepA; }
-        else { dma16(base + DSTAGE_BYTES + (i - 2) * 1024, voB[i - 2], rsB); voB[i - 2] += stepB; }
+        if (i < 4) { dma16(base + i * 1024, voA[i], rsA); voA[i] += stepA; }
+        else { dma16(base + DSTAGE_BYTES + (i - 4) * 1024, voB[i - 4], rsB); voB[i - 4] += stepB; }
     };
-    // point the DMA offsets at tile (m0, n0) and put its first three k tiles on their way
+    // point the DMA offsets at tile (m0, n0) and put its first two k tiles on their way
     auto start_tile = [&](int m0, int n0) {
 #pragma unroll
-        for (int i = 0; i < 2; i++) { voA[i] = DA::voff(i, m0, lda) + kbeg * stepA; voB[i] = DB::voff(i, n0, ldb) + kbeg * stepB; }
+        for (int i = 0; i < 4; i++) { voA[i] = DA::voff(i, m0, lda) + kbeg * stepA; voB[i] = DB::voff(i, n0, ldb) + kbeg * stepB; }
 #pragma unroll
-        for (int s = 0; s < DSTAGES - 1; s++)
+        for (int s = 0; s < 2; s++)
             if (s < nk) {
 #pragma unroll
-                for (int i = 0; i < 4; i++) dma_part(s, i);
+                for (int i = 0; i < 8; i++) dma_part(s, i);
             }
     };
 
@@ -364,8 +366,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
 
         // k tile 0 landed.  After an epilogue its stores sit behind the DMAs in the memory queue, so the
         // count-based wait only applies to a fresh start.
-        if (fresh && nk > 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (fresh && nk > 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (fresh && nk > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
@@ -375,33 +376,44 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
         for (int j = 0; j < TN; j++) b0[j] = DB::frag(smem + DSTAGE_BYTES, wn + 32 * j, 0);
 
         for (int kt = 0; kt < nk; kt++) {
-            // tile kt+1 must have landed (it is read before the next barrier); only tile kt+2 may be outstanding
-            if (kt + 2 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();   // tile kt+1 complete in LDS for everyone; everyone is done reading tile kt-1
-            const char* cA = smem + (kt & 3) * (2 * DSTAGE_BYTES);
+            const char* cA = smem + (kt & 1) * (2 * DSTAGE_BYTES);
             const char* cB = cA + DSTAGE_BYTES;
-            const char* nA = smem + ((kt + 1) & 3) * (2 * DSTAGE_BYTES);
+            const char* nA = smem + ((kt + 1) & 1) * (2 * DSTAGE_BYTES);
             const char* nB = nA + DSTAGE_BYTES;
-            const bool more = kt + 3 < nk, next = kt + 1 < nk;
-            const int st3 = (kt + 3) & 3;
+            const bool more = kt + 2 < nk;
             SB();
-            // k step 0 of tile kt: MFMAs on (a0, b0); meanwhile fetch the k step 1 fragments and issue tile kt+3
+            // k steps 0..2 of tile kt: MFMAs on one fragment set while the next one is fetched
 #pragma unroll
-            for (int i = 0; i < TM; i++) {
+            for (int kk = 0; kk < 3; kk++) {
+                bf16x8 (&ca)[TM] = (kk & 1) ? a1 : a0;
+                bf16x8 (&cb)[TN] = (kk & 1) ? b1 : b0;
+                bf16x8 (&na)[TM] = (kk & 1) ? a0 : a1;
+                bf16x8 (&nb)[TN] = (kk & 1) ? b0 : b1;
 #pragma unroll
-                for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0[j], a0[i], acc[i][j], 0, 0, 0);
-                a1[i] = DA::frag(cA, wm + 32 * i, 1);
-                if (i < TN) b1[i] = DB::frag(cB, wn + 32 * i, 1);
-                if (more) dma_part(st3, i);
-                SB();
+                for (int i = 0; i < TM; i++) {
+#pragma unroll
+                    for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
+                    if (i == 0) { na[0] = DA::frag(cA, wm, kk + 1); nb[0] = DB::frag(cB, wn, kk + 1); nb[1] = DB::frag(cB, wn + 32, kk + 1); }
+                    if (i == 1) { na[1] = DA::frag(cA, wm + 32, kk + 1); na[2] = DA::frag(cA, wm + 64, kk + 1); }
+                    if (i == 2) { na[3] = DA::frag(cA, wm + 96, kk + 1); }
+                    SB();
+                }
             }
-            // k step 1: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1
+            // Every wave now holds its last fragments of tile kt, so the stage of tile kt is free once all
+            // waves are here; tile kt+1 (issued one tile ago) must have landed for everyone.
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            SB();
+            // k step 3: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1 and issue tile kt+2
 #pragma unroll
             for (int i = 0; i < TM; i++) {
 #pragma unroll
                 for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1[j], a1[i], acc[i][j], 0, 0, 0);
-                if (next) { a0[i] = DA::frag(nA, wm + 32 * i, 0); if (i < TN) b0[i] = DB::frag(nB, wn + 32 * i, 0); }
+                if (i == 0) { a0[0] = DA::frag(nA, wm, 0); b0[0] = DB::frag(nB, wn, 0); b0[1] = DB::frag(nB, wn + 32, 0); }
+                if (i == 1) { a0[1] = DA::frag(nA, wm + 32, 0); a0[2] = DA::frag(nA, wm + 64, 0); }
+                if (i == 2) { a0[3] = DA::frag(nA, wm + 96, 0); }
+                if (more) { dma_part(kt & 1, 2 * i); dma_part(kt & 1, 2 * i + 1); }
                 SB();
             }
         }
@@ -566,7 +578,7 @@ static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_byt
     if (rem > 0 && rem <= NUM_CU / 2 && g.ws) {
         int s = NUM_CU / rem;
         if (s > 8) s = 8;
-        while (s > 1 && (nk / s < 8 || (size_t)rem * s * DTILE * DTILE * sizeof(float) > g.ws_bytes)) s--;
+        while (s > 1 && (nk / s < 4 || (size_t)rem * s * DTILE * DTILE * sizeof(float) > g.ws_bytes)) s--;
         if (s > 1) { full = tiles - rem; tail = rem; ksplit = s; }
     }
     if (full > 0)   // one workgroup per CU walks its share of the tiles
@@ -599,6 +611,8 @@ hipError_t gemm_bf16(const GemmDesc& g, hipStream_t st) {
     const long a_bytes = ((a_rows - 1) * g.lda + a_cols) * 2, b_bytes = ((b_rows - 1) * g.ldb + b_cols) * 2;
     if (a_bytes >= (1L << 32) - (1L << 25) || b_bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
     if (g.lda > 65535 || g.ldb > 65535) return hipErrorInvalidValue;
+    // a k-contiguous operand is fetched 64 k values at a time with no per-row bound
+    if (g.kind != GEMM_TN && g.K % 64 != 0) return hipErrorInvalidValue;
     // activations come out in bf16 (NT, NN), parameter gradients in fp32 (TN)
     if ((g.out_f32 != 0) != (g.kind == GEMM_TN) || (g.out_f32 && g.R)) return hipErrorInvalidValue;
     switch (g.kind) {
