@@ -179,8 +179,11 @@ int hh_layer_profile(hh_ctx *ctx, const hh_layer_cfg *cfg, int n_layers, const h
 
 /* Per-kernel-family timing of whatever the hot calls enqueue (the measurement
  * side of the automatic profiling of Section 3.2).  Between hh_trace_begin and
- * hh_trace_end every launch is bracketed by HIP events on its stream, up to
- * max_launches launches (later ones are not recorded).  hh_trace_begin creates
+ * hh_trace_end every launch of a family whose bit (1u << kind) is set in
+ * kind_mask is bracketed by HIP events on its stream, up to max_launches
+ * launches (later ones are not recorded).  Events between kernels cost a few
+ * microseconds each, so a caller that times a whole step selects only the
+ * families it needs.  hh_trace_begin creates
  * the events (not a hot call); hh_trace_end waits for them and fills
  * out[0..n_kinds-1] (HOST) with launch count, summed milliseconds and summed
  * work: model flops for GEMM and attention families, algorithmic bytes for the
@@ -200,7 +203,7 @@ typedef struct {
     double ms;
     double work;
 } hh_trace_sum;
-int hh_trace_begin(hh_ctx *ctx, int max_launches);
+int hh_trace_begin(hh_ctx *ctx, int max_launches, uint32_t kind_mask);
 int hh_trace_end(hh_ctx *ctx, hh_trace_sum *out, int n_kinds);
 
 #ifdef __cplusplus

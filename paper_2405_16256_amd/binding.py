@@ -84,7 +84,7 @@ def _load() -> C.CDLL:
         "hh_stage_sizes": [cfgp, i, i, sz, sz],
         "hh_stage_step": [vp, cfgp, i, wp, i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), gp, i, vp, vp, vp],
         "hh_layer_profile": [vp, cfgp, i, wp, gp, vp, vp, i, i, vp, vp, C.POINTER(hh_profile_rec), vp],
-        "hh_trace_begin": [vp, i],
+        "hh_trace_begin": [vp, i, C.c_uint32],
         "hh_trace_end": [vp, C.POINTER(hh_trace_sum), i],
     }
     for name, args in sigs.items():
@@ -194,8 +194,10 @@ def hh_layer_profile(ctx, cfg, weights: Sequence[hh_layer_weights], grads: Seque
     return list(out)
 
 
-def hh_trace_begin(ctx, max_launches: int) -> None:
-    _check(lib.hh_trace_begin(ctx, max_launches))
+def hh_trace_begin(ctx, max_launches: int, kinds=None) -> None:
+    """kinds: family names from TRACE_KINDS to record (None: all)."""
+    mask = 0xFFFFFFFF if kinds is None else sum(1 << TRACE_KINDS.index(k) for k in kinds)
+    _check(lib.hh_trace_begin(ctx, max_launches, mask))
 
 
 def hh_trace_end(ctx) -> dict:

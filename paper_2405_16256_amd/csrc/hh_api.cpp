@@ -75,6 +75,7 @@ struct hh_ctx {
     std::vector<TraceRec> trace;  // events created by hh_trace_begin
     size_t trace_used;
     bool trace_on;
+    uint32_t trace_mask;          // families recorded while trace_on
     void* gemm_ws;                // k-split scratch inside the caller's workspace, set by each hot call
 };
 
@@ -85,7 +86,7 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess) return hip_fail(e, "hipGetDeviceCount");
     if (device < 0 || device >= n) return fail(HH_ERR_DEVICE, "hh_ctx_create: no HIP device %d (%d visible)", device, n);
-    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false, nullptr};
+    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false, 0u, nullptr};
     if (!c) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out of host memory");
     *out = c;
     return HH_OK;
@@ -274,7 +275,7 @@ extern "C" int hh_ctx_reserve(hh_ctx* ctx, const hh_layer_cfg* cfg) {
 struct Traced {
     hh_ctx* ctx; hipStream_t st; TraceRec* rec;
     Traced(hh_ctx* c, hipStream_t s, int kind, double work) : ctx(c), st(s), rec(nullptr) {
-        if (c->trace_on && c->trace_used < c->trace.size()) {
+        if (c->trace_on && ((c->trace_mask >> kind) & 1u) && c->trace_used < c->trace.size()) {
             rec = &c->trace[c->trace_used++];
             rec->kind = kind; rec->work = work;
             (void)hipEventRecord(rec->a, st);
@@ -295,7 +296,7 @@ static hipError_t tgemm(hh_ctx* ctx, int dt, GemmDesc g, hipStream_t st) {
     return gemm(dt, g, st);
 }
 
-extern "C" int hh_trace_begin(hh_ctx* ctx, int max_launches) {
+extern "C" int hh_trace_begin(hh_ctx* ctx, int max_launches, uint32_t kind_mask) {
     if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
     if (max_launches <= 0) return fail(HH_ERR_INVALID_ARG, "max_launches must be positive");
     HIP_TRY(hipSetDevice(ctx->device));
@@ -307,6 +308,7 @@ extern "C" int hh_trace_begin(hh_ctx* ctx, int max_launches) {
         ctx->trace.push_back(r);
     }
     ctx->trace_used = 0;
+    ctx->trace_mask = kind_mask;
     ctx->trace_on = true;
     return HH_OK;
 }

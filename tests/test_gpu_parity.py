@@ -345,3 +345,39 @@ def test_layer_profile_records(ctx):
         assert r.p2p_bytes == 2 * s.micro_batch * s.seq * s.hidden      # Eq. (3)
         assert r.saved_act_bytes > 0
     say("  profile: " + ", ".join("L%d f=%.3fms b=%.3fms" % (r.layer, r.fwd_ms, r.bwd_ms) for r in recs))
+
+
+def test_trace_counts_launches_per_family_and_honours_the_mask(ctx):
+    s = I.LayerShape(512, 4, 128, 1024, 256, 1)
+    cfg = L.cfg_of(s, True)
+    layer = L.DeviceLayer(I.layer_weights(52, 0, s, True), s, True)
+    x_np, dy_np = I.activations(52, s, 0, True)
+    x, dy = L.to_dev(x_np, True), L.to_dev(dy_np, True)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    pool_b, wsb = hh.hh_stage_sizes(cfg, 1, 1)
+    pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
+    wsp = torch.empty(wsb, dtype=torch.uint8, device=L.DEV)
+
+    def step():
+        hh.hh_stage_step(ctx, cfg, [layer.wstruct], [x], [y], [dy], [dx], [layer.gstruct], 1, pool, wsp, L.stream_ptr())
+
+    hh.hh_trace_begin(ctx, 200)
+    step()
+    step()
+    fam = hh.hh_trace_end(ctx)
+    f, b = hh.hh_layer_flops(cfg)
+    # per layer pass: 4 forward GEMMs, 4 input-gradient GEMMs, 4 weight-gradient GEMMs, one attention each way
+    assert [fam[n][0] for n in ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd")] == [8, 8, 8, 2, 2]
+    assert fam["elementwise"][0] > 0 and all(v[1] > 0 for v in fam.values())
+    flops = sum(fam[n][2] for n in ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd"))
+    assert abs(flops - 2 * (f + b)) <= 1e-9 * flops
+    hh.hh_trace_begin(ctx, 200, ["gemm_tn"])
+    step()
+    fam = hh.hh_trace_end(ctx)
+    assert fam["gemm_tn"][0] == 4 and fam["gemm_tn"][1] > 0
+    assert all(v[0] == 0 for n, v in fam.items() if n != "gemm_tn")
+    # nothing is recorded once the trace has ended
+    step()
+    hh.hh_trace_begin(ctx, 1, ["attn_fwd"])
+    fam = hh.hh_trace_end(ctx)
+    assert all(v[0] == 0 for v in fam.values())
