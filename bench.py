@@ -20,6 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
+# HBM-side bytes per GEMM call of the weight-gradient family at the default workload, from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE passes over this command, scaled by a 1 GiB copy (x2.000 and x1.000): 1.091 GB fetched + 0.299 GB
+# written.  Holds for the kernel build those passes ran on; None for anything else.
+TRAFFIC_BYTES_PER_LAUNCH = {("cfg3", "gemm_tn"): 1.391e9}
 
 
 def workloads():
@@ -130,7 +134,8 @@ def main():
         achieved = dwork / (dms * 1e-3) / 1e12
         roofline = {"kernel": "k_gemm_dma (%s; one launch = one GEMM call incl. its k-split tail)" % dom, "bound": "mfma",
                     "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None, "launches": launches,
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((a.workload, dom)),
+                    "traffic_unit": "bytes per launch", "launches": launches,
                     "avg_launch_ms": round(dms / launches, 4), "flop_per_launch": dwork / launches,
                     "ms_per_step": round(dms / a.steps, 4)}
 
