@@ -7,7 +7,7 @@ workload, one 140B-class TP=8-share decoder layer, one micro-batch of 4096
 tokens: forward, then backward with fp32 gradient accumulation), every kernel
 hand-written HIP behind the C-ABI.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg4-1f1b] [--no-cpu-baseline]
 """
 import argparse
 import json
@@ -36,6 +36,8 @@ def workloads():
                           "seq 4096, micro-batch 1, bf16 fwd+bwd"),
         "cfg4": dict(shape=I.CFG3, k=4, M=8, seed=I.SEEDS["cfg4"],
                      name="cfg4: pipeline-stage step, 4 layers of the cfg3 shape x 8 micro-batches of seq 4096, fp32 grad accumulation"),
+        "cfg4-1f1b": dict(shape=I.CFG3, k=4, M=8, live=2, seed=I.SEEDS["cfg4"],
+                          name="cfg4 in one-forward-one-backward order with 2 live micro-batches (activation pool a quarter of cfg4's)"),
     }
 
 
@@ -44,7 +46,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4-1f1b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-trace", action="store_true", help="do not time kernel families with events (no roofline object)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -76,7 +78,8 @@ def main():
     dys = [L.to_dev(acts[m % len(acts)][1], True) for m in range(M)]
     ys = [torch.empty_like(t) for t in xs]
     dxs = [torch.empty_like(t) for t in xs]
-    pool_b, ws_b = hh.hh_stage_sizes(cfg, k, M)
+    live = wl.get("live", M)
+    pool_b, ws_b = hh.hh_stage_sizes(cfg, k, live)
     pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
     wsp = torch.empty(ws_b, dtype=torch.uint8, device=L.DEV)
     print("[bench] inputs ready in %.1fs; pool %.2f GB" % (time.time() - t0, pool_b / 1e9), file=sys.stderr, flush=True)
@@ -86,7 +89,10 @@ def main():
 
     def step():
         # steady-state training: gradients accumulate, nothing is zeroed inside the timed region
-        hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
+        if live == M:
+            hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
+        else:
+            hh.hh_stage_step_1f1b(ctx, cfg, wst, live, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
 
     if a.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=L.DEV).fill_(1)
@@ -143,7 +149,7 @@ def main():
         "metric": "decoder-layer fwd+bwd TFLOP/s on 1 GPU", "value": round(tflops, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl["name"], "layers": k, "micro_batches": M, "tokens_per_micro_batch": s.tokens,
+        "config": {"workload": wl["name"], "layers": k, "micro_batches": M, "live_micro_batches": live, "activation_pool_bytes": pool_b, "tokens_per_micro_batch": s.tokens,
                    "model_flop_per_step": flop_step},
         "tokens_per_s": round(tokens_s, 1),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),

@@ -165,6 +165,22 @@ int hh_stage_step(hh_ctx *ctx, const hh_layer_cfg *cfg, int n_layers, const hh_l
                   const hh_layer_grads *g, int zero_grads_first,
                   void *saved_pool, void *workspace, void *stream);
 
+/* The same step in one-forward-one-backward order (PipeDream-1F1B, Section 2.3,
+ * the scheme whose data constraints the pipeline of Section 3.3 keeps): forward
+ * of micro-batches 0..n_live-1, then for m = 0..n_micro-1 backward of m followed
+ * by forward of m + n_live.  At most n_live micro-batches' activations are alive,
+ * so saved_pool is sized by hh_stage_sizes(cfg, n_layers, n_live): that figure
+ * is the stage's activation high-water mark.  In a pipeline of P stages the
+ * stage of rank r uses n_live = min(n_micro, P - r).  1 <= n_live <= n_micro;
+ * n_live == n_micro is hh_stage_step.  Backward visits the micro-batches in
+ * ascending order in both, so the results are bit-identical to hh_stage_step.
+ * y[m + n_live] is written while dy[m + 1 ...] are still to be read: y and dy
+ * arrays must not share buffers across micro-batches. */
+int hh_stage_step_1f1b(hh_ctx *ctx, const hh_layer_cfg *cfg, int n_layers, const hh_layer_weights *w,
+                       int n_micro, int n_live, const void *const *x, void *const *y,
+                       const void *const *dy, void *const *dx, const hh_layer_grads *g,
+                       int zero_grads_first, void *saved_pool, void *workspace, void *stream);
+
 /* Time every layer of a stage (Sections 1 and 3.2: automatic profiling that
  * feeds the predictor).  Runs the stage on x / dy (device, [B,S,H]) with
  * `warmup` untimed and `iters` timed repetitions, bracketing each layer's

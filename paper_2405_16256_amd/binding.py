@@ -28,7 +28,7 @@ HH_BF16 = 1
 
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
-           "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_layer_profile", "hh_trace_begin",
+           "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
            "hh_trace_end")
 TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
@@ -83,6 +83,8 @@ def _load() -> C.CDLL:
         "hh_layer_bwd": [vp, cfgp, wp, vp, vp, vp, vp, gp, i, vp, vp],
         "hh_stage_sizes": [cfgp, i, i, sz, sz],
         "hh_stage_step": [vp, cfgp, i, wp, i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), gp, i, vp, vp, vp],
+        "hh_stage_step_1f1b": [vp, cfgp, i, wp, i, i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), gp, i, vp, vp,
+                               vp],
         "hh_layer_profile": [vp, cfgp, i, wp, gp, vp, vp, i, i, vp, vp, C.POINTER(hh_profile_rec), vp],
         "hh_trace_begin": [vp, i, C.c_uint32],
         "hh_trace_end": [vp, C.POINTER(hh_trace_sum), i],
@@ -181,6 +183,16 @@ def hh_stage_step(ctx, cfg, weights: Sequence[hh_layer_weights], x: Sequence, y:
     garr = (hh_layer_grads * k)(*grads)
     _check(lib.hh_stage_step(ctx, C.byref(cfg), k, warr, m, _ptr_array(x), _ptr_array(y), _ptr_array(dy), _ptr_array(dx),
                              garr, int(zero_grads_first), _ptr(saved_pool), _ptr(workspace), stream))
+
+
+def hh_stage_step_1f1b(ctx, cfg, weights: Sequence[hh_layer_weights], n_live: int, x: Sequence, y: Sequence, dy: Sequence,
+                       dx: Sequence, grads: Sequence[hh_layer_grads], zero_grads_first, saved_pool, workspace, stream=0) -> None:
+    k, m = len(weights), len(x)
+    assert len(grads) == k and len(y) == m and len(dy) == m and len(dx) == m
+    warr = (hh_layer_weights * k)(*weights)
+    garr = (hh_layer_grads * k)(*grads)
+    _check(lib.hh_stage_step_1f1b(ctx, C.byref(cfg), k, warr, m, int(n_live), _ptr_array(x), _ptr_array(y), _ptr_array(dy),
+                                  _ptr_array(dx), garr, int(zero_grads_first), _ptr(saved_pool), _ptr(workspace), stream))
 
 
 def hh_layer_profile(ctx, cfg, weights: Sequence[hh_layer_weights], grads: Sequence[hh_layer_grads], x, dy, warmup, iters,

@@ -510,11 +510,38 @@ static int check_stage_args(const hh_layer_cfg* cfg, int n_layers, const hh_laye
     return HH_OK;
 }
 
-extern "C" int hh_stage_step(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w, int n_micro,
-                             const void* const* x, void* const* y, const void* const* dy, void* const* dx,
-                             const hh_layer_grads* g, int zero_grads_first, void* saved_pool, void* workspace, void* stream) {
+// Forward of micro-batch m through the stage, activations into pool slot `slot`.
+static int stage_fwd(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, int k, const hh_layer_weights* w, const StagePool& p,
+                     int slot, const void* x, void* y, void* workspace, hipStream_t st) {
+    for (int l = 0; l < k; l++) {
+        const void* in = l == 0 ? x : p.act(slot, l - 1);
+        void* out = l == k - 1 ? y : p.act(slot, l);
+        TRY(layer_fwd_impl(ctx, d, cfg, &w[l], in, out, p.saved(slot, l), workspace, st));
+    }
+    return HH_OK;
+}
+// Backward of the micro-batch whose activations sit in pool slot `slot`.
+static int stage_bwd(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, int k, const hh_layer_weights* w, const hh_layer_grads* g,
+                     const StagePool& p, int slot, const void* x, const void* dy, void* dx, int acc, void* workspace, hipStream_t st) {
+    void* gbuf = at(workspace, work_layout(d).total);  // gradient flowing between layers, updated in place
+    for (int l = k - 1; l >= 0; l--) {
+        const void* in = l == 0 ? x : p.act(slot, l - 1);
+        const void* gin = l == k - 1 ? dy : gbuf;
+        void* gout = l == 0 ? dx : gbuf;
+        TRY(layer_bwd_impl(ctx, d, cfg, &w[l], in, p.saved(slot, l), gin, gout, &g[l], acc, workspace, st));
+    }
+    return HH_OK;
+}
+
+// Both schedules: forward of the first n_live micro-batches, then backward of m followed by forward of
+// m + n_live.  n_live == n_micro is "all forwards, then all backwards".  Backward always visits the
+// micro-batches in ascending order, so the fp32 sums are formed in the same order for every n_live.
+static int stage_run(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w, int n_micro, int n_live,
+                     const void* const* x, void* const* y, const void* const* dy, void* const* dx, const hh_layer_grads* g,
+                     int zero_grads_first, void* saved_pool, void* workspace, void* stream) {
     TRY(check_stage_args(cfg, n_layers, w, g));
     if (n_micro <= 0) return fail(HH_ERR_INVALID_ARG, "n_micro must be positive");
+    if (n_live <= 0 || n_live > n_micro) return fail(HH_ERR_INVALID_ARG, "n_live must be in 1..n_micro (got %d, n_micro %d)", n_live, n_micro);
     if (!x || !y || !dy || !dx) return fail(HH_ERR_INVALID_ARG, "x / y / dy / dx pointer array is NULL");
     for (int m = 0; m < n_micro; m++) {
         TRY(check_ptr(x[m], "x[m]")); TRY(check_ptr(y[m], "y[m]")); TRY(check_ptr(dy[m], "dy[m]")); TRY(check_ptr(dx[m], "dx[m]"));
@@ -526,22 +553,28 @@ extern "C" int hh_stage_step(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers,
     const Dims d = dims_of(cfg);
     const StagePool p = stage_pool(d, n_layers, saved_pool);
     hipStream_t st = (hipStream_t)stream;
-    for (int m = 0; m < n_micro; m++)
-        for (int l = 0; l < n_layers; l++) {
-            const void* in = l == 0 ? x[m] : p.act(m, l - 1);
-            void* out = l == n_layers - 1 ? y[m] : p.act(m, l);
-            TRY(layer_fwd_impl(ctx, d, cfg, &w[l], in, out, p.saved(m, l), workspace, st));
-        }
-    void* gbuf = at(workspace, work_layout(d).total);  // gradient flowing between layers, updated in place
-    for (int m = 0; m < n_micro; m++)
-        for (int l = n_layers - 1; l >= 0; l--) {
-            const void* in = l == 0 ? x[m] : p.act(m, l - 1);
-            const void* gin = l == n_layers - 1 ? dy[m] : gbuf;
-            void* gout = l == 0 ? dx[m] : gbuf;
-            const int acc = (m > 0 || !zero_grads_first) ? 1 : 0;
-            TRY(layer_bwd_impl(ctx, d, cfg, &w[l], in, p.saved(m, l), gin, gout, &g[l], acc, workspace, st));
-        }
+    for (int m = 0; m < n_live; m++) TRY(stage_fwd(ctx, d, cfg, n_layers, w, p, m, x[m], y[m], workspace, st));
+    for (int m = 0; m < n_micro; m++) {
+        const int acc = (m > 0 || !zero_grads_first) ? 1 : 0;
+        const int slot = m % n_live;
+        TRY(stage_bwd(ctx, d, cfg, n_layers, w, g, p, slot, x[m], dy[m], dx[m], acc, workspace, st));
+        const int nxt = m + n_live;   // its activations take the slot just released
+        if (nxt < n_micro) TRY(stage_fwd(ctx, d, cfg, n_layers, w, p, slot, x[nxt], y[nxt], workspace, st));
+    }
     return HH_OK;
+}
+
+extern "C" int hh_stage_step(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w, int n_micro,
+                             const void* const* x, void* const* y, const void* const* dy, void* const* dx,
+                             const hh_layer_grads* g, int zero_grads_first, void* saved_pool, void* workspace, void* stream) {
+    return stage_run(ctx, cfg, n_layers, w, n_micro, n_micro, x, y, dy, dx, g, zero_grads_first, saved_pool, workspace, stream);
+}
+
+extern "C" int hh_stage_step_1f1b(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_layers, const hh_layer_weights* w, int n_micro,
+                                  int n_live, const void* const* x, void* const* y, const void* const* dy, void* const* dx,
+                                  const hh_layer_grads* g, int zero_grads_first, void* saved_pool, void* workspace,
+                                  void* stream) {
+    return stage_run(ctx, cfg, n_layers, w, n_micro, n_live, x, y, dy, dx, g, zero_grads_first, saved_pool, workspace, stream);
 }
 
 // ------------------------------------------------------------------ profile

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     src = open(os.path.join(ROOT, "include", "hh.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(hh_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(hh_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -122,6 +122,14 @@ def test_pointer_validation_happens_before_any_gpu_work():
     with pytest.raises(hh.HHError) as e:
         hh.hh_stage_step(None, cfg, [w], [ok], [2 * ok], [ok], [ok], [g], 1, None, ok)
     assert e.value.code == hh.HH_ERR_INVALID_ARG and "saved_pool" in str(e.value)
+    # one-forward-one-backward order: 1 <= n_live <= n_micro
+    for n_live in (0, 3):
+        with pytest.raises(hh.HHError) as e:
+            hh.hh_stage_step_1f1b(None, cfg, [w], n_live, [ok, ok], [2 * ok, 2 * ok], [ok, ok], [ok, ok], [g], 1, ok, ok)
+        assert e.value.code == hh.HH_ERR_INVALID_ARG and "n_live" in str(e.value)
+    with pytest.raises(hh.HHError) as e:
+        hh.hh_stage_step_1f1b(None, cfg, [w], 1, [ok, ok], [2 * ok, 2 * ok], [ok, ok], [ok, ok], [g], 1, ok, ok)
+    assert e.value.code == hh.HH_ERR_INVALID_ARG and "ctx" in str(e.value)
     with pytest.raises(hh.HHError) as e:
         hh.hh_stage_sizes(cfg, 0, 1)
     assert e.value.code == hh.HH_ERR_INVALID_ARG

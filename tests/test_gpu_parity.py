@@ -266,6 +266,65 @@ def test_stage_step_full_size_four_layers_eight_micro_batches_equals_chained_cal
         for n in I.WEIGHT_NAMES:
             assert torch.equal(layers[l].g[n], ref_layers[l].g[n]), (l, n)
             assert torch.isfinite(layers[l].g[n]).all()
+    # the same step in one-forward-one-backward order with two live micro-batches (a quarter of the pool)
+    del wsp2
+    n_live = 2
+    pool_b2, _ = hh.hh_stage_sizes(cfg, k, n_live)
+    assert pool_b2 * M == pool_b * n_live
+    say("  1F1B pool %.2f GB" % (pool_b2 / 1e9))
+    pool2 = torch.empty(pool_b2, dtype=torch.uint8, device=L.DEV)
+    ys2 = [torch.full_like(t, float("nan")) for t in xs]
+    dxs2 = [torch.full_like(t, float("nan")) for t in xs]
+    hh.hh_stage_step_1f1b(ctx, cfg, [l.wstruct for l in ref_layers], n_live, xs, ys2, dys, dxs2, [l.gstruct for l in ref_layers],
+                          1, pool2, wsp, st)
+    torch.cuda.synchronize()
+    for m in range(M):
+        assert torch.equal(ys2[m], ys[m]) and torch.equal(dxs2[m], dxs[m]), m
+    for l in range(k):
+        for n in I.WEIGHT_NAMES:
+            assert torch.equal(layers[l].g[n], ref_layers[l].g[n]), (l, n)
+
+
+@pytest.mark.parametrize("n_live", [1, 2, 3, 5])
+def test_one_forward_one_backward_order_is_bit_identical_and_matches_oracle(ctx, n_live):
+    """Section 2.3: 1F1B keeps at most n_live micro-batches' activations.  Backward order over micro-batches is
+    the same as in the all-forward-all-backward step, so every output must be identical bit for bit."""
+    s, k, M, bf16 = I.LayerShape(256, 2, 128, 320, 136, 2), 3, 5, True
+    say("[case] 1F1B n_live=%d shape=%s k=%d M=%d" % (n_live, s, k, M))
+    ws_np, acts, layers, ys, dxs = run_stage(ctx, s, bf16, 44, k, M)
+    cfg = L.cfg_of(s, bf16)
+    layers2 = [L.DeviceLayer(w, s, bf16) for w in ws_np]
+    for l in layers2:                        # zero_grads_first must overwrite whatever the buffers hold
+        for n in I.WEIGHT_NAMES:
+            l.g[n].fill_(7.0)
+    xs = [L.to_dev(a[0], bf16) for a in acts]
+    dys = [L.to_dev(a[1], bf16) for a in acts]
+    ys2 = [torch.full_like(t, float("nan")) for t in xs]
+    dxs2 = [torch.full_like(t, float("nan")) for t in xs]
+    pool_b, wsb = hh.hh_stage_sizes(cfg, k, n_live)
+    full_b, _ = hh.hh_stage_sizes(cfg, k, M)
+    assert pool_b * M == full_b * n_live
+    pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
+    wsp = torch.empty(wsb, dtype=torch.uint8, device=L.DEV)
+    hh.hh_stage_step_1f1b(ctx, cfg, [l.wstruct for l in layers2], n_live, xs, ys2, dys, dxs2, [l.gstruct for l in layers2], 1,
+                          pool, wsp, L.stream_ptr())
+    torch.cuda.synchronize()
+    for m in range(M):
+        assert torch.equal(ys2[m], ys[m]) and torch.equal(dxs2[m], dxs[m]), m
+    for l in range(k):
+        for n in I.WEIGHT_NAMES:
+            assert torch.equal(layers2[l].g[n], layers[l].g[n]), (l, n)
+    if n_live == 2:
+        yo, dxo, go = O.stage_step([a[0] for a in acts], [a[1] for a in acts], ws_np, s.n_heads, s.head_dim, s.rms_eps,
+                                   s.rope_base)
+        for m in range(M):
+            assert L.rel_err(L.to_np(ys2[m]), yo[m]) <= TOL_BF16_OUT
+            assert L.rel_err(L.to_np(dxs2[m]), dxo[m]) <= TOL_BF16_GRAD
+        for l in range(k):
+            gl = layers2[l].grads_np()
+            for n in I.WEIGHT_NAMES:
+                e = L.rel_err(gl[n], go[l][n])
+                assert e <= TOL_BF16_GRAD, (l, n, e)
 
 
 def test_stage_step_equals_chained_layer_calls_bitwise(ctx):
