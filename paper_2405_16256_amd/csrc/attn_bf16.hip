@@ -148,11 +148,14 @@ __device__ __forceinline__ void load_qfrag(bf16x8 (&f)[D / 16], __amdgpu_buffer_
 // ------------------------------------------------------------------ forward
 template <int D>
 __global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
-                                                       bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh) {
+                                                       bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh, int B) {
     using TL = Tile<D>;
     constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
     extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // flattened grid, last query block first: the long jobs of every head and sample are dispatched
+    // before the short ones
+    const int nhb = nh * B;
+    const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int q0 = qb * 128 + wave * 32;
@@ -292,11 +295,12 @@ template <int D>
 __global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                           const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                           const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                          bf16_t* __restrict__ dqkv, int S, int nh) {
+                                                          bf16_t* __restrict__ dqkv, int S, int nh, int B) {
     using TL = Tile<D>;
     constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
     extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
-    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int nhb = nh * B;   // flattened grid, last query block first (see k_attn_fwd)
+    const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int q0 = qb * 128 + wave * 32;
@@ -567,8 +571,8 @@ static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float*
     constexpr int LDS = 4 * Tile<D>::BYTES;
     hipError_t e = set_lds(k_attn_fwd<D>, LDS);
     if (e != hipSuccess) return e;
-    dim3 grid((S + 127) / 128, nh, B);
-    k_attn_fwd<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh);
+    const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
+    k_attn_fwd<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, B);
     return hipGetLastError();
 }
 
@@ -580,12 +584,12 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
     if (e != hipSuccess) return e;
     e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
     if (e != hipSuccess) return e;
-    dim3 grid((S + 127) / 128, nh, B);
+    const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
     const long rows = (long)B * S * nh;
     k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
     k_attn_bwd_dq<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                  (bf16_t*)dqkv, S, nh);
-    k_attn_bwd_dkv<D><<<dim3(grid.x * nh * B), KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
+                                                  (bf16_t*)dqkv, S, nh, B);
+    k_attn_bwd_dkv<D><<<grid, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
                                                                          dvec, (bf16_t*)dqkv, S, nh, B);
     return hipGetLastError();
 }
