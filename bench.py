@@ -7,7 +7,7 @@ workload, one 140B-class TP=8-share decoder layer, one micro-batch of 4096
 tokens: forward, then backward with fp32 gradient accumulation), every kernel
 hand-written HIP behind the C-ABI.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg4-1f1b] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg4-1f1b|13b|h8192-tp8] [--no-cpu-baseline]
 """
 import argparse
 import json
@@ -34,6 +34,11 @@ def workloads():
         "cfg3": dict(shape=I.CFG3, k=1, M=1, seed=I.SEEDS["cfg3"],
                      name="cfg3: 140B-class decoder layer at a TP=8 share, hidden 12288, 12x128 local heads, local ffn 4096, "
                           "seq 4096, micro-batch 1, bf16 fwd+bwd"),
+        "13b": dict(shape=I.SHAPE_13B, k=1, M=1, seed=61,
+                    name="13B-class decoder layer, hidden 5120, 40x128 heads, ffn 13824, seq 2048, micro-batch 1, bf16 fwd+bwd"),
+        "h8192-tp8": dict(shape=I.SHAPE_70B_TP8, k=1, M=1, seed=62,
+                          name="hidden-8192 (70B/140B-class of Table 1) decoder layer at a TP=8 share, 8x128 local heads, local ffn 3584, "
+                               "seq 4096, micro-batch 1, bf16 fwd+bwd"),
         "cfg4": dict(shape=I.CFG3, k=4, M=8, seed=I.SEEDS["cfg4"],
                      name="cfg4: pipeline-stage step, 4 layers of the cfg3 shape x 8 micro-batches of seq 4096, fp32 grad accumulation"),
         "cfg4-1f1b": dict(shape=I.CFG3, k=4, M=8, live=2, seed=I.SEEDS["cfg4"],
@@ -46,7 +51,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4-1f1b"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4-1f1b", "13b", "h8192-tp8"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-trace", action="store_true", help="do not time kernel families with events (no roofline object)")
     ap.add_argument("--copy-calibration", action="store_true",

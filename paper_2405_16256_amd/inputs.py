@@ -123,6 +123,10 @@ class LayerShape:
 CFG1 = LayerShape(256, 4, 64, 688, 128, 1)          # tiny, fp32
 CFG2 = LayerShape(4096, 32, 128, 11008, 2048, 1)    # 7B-class layer, bf16
 CFG3 = LayerShape(12288, 12, 128, 4096, 4096, 1)    # 140B-class layer at a TP=8 share, bf16
+# further Table 1 model classes (hidden size from the table; head count and FFN width are the public
+# Llama-2 values for that hidden size, which the paper does not state)
+SHAPE_13B = LayerShape(5120, 40, 128, 13824, 2048, 1)        # 13B-class layer: 40 x 128 heads
+SHAPE_70B_TP8 = LayerShape(8192, 8, 128, 3584, 4096, 1)      # 70B/140B-class hidden 8192 at a TP=8 share (MHA)
 SEEDS = {"cfg1": 1001, "cfg2": 1002, "cfg3": 1003, "cfg4": 1004, "cfg5": 1005}
 
 

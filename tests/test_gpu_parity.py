@@ -112,6 +112,17 @@ def test_bf16_140b_class_tp_share_full_size(ctx):
     check_layer(ctx, I.CFG3, True, I.SEEDS["cfg3"], label="cfg3")
 
 
+def test_bf16_13b_class_layer_full_size(ctx):
+    # hidden 5120 (Table 1): 20 x 20 tiles of 256 leave k-split tails in every GEMM family
+    check_layer(ctx, I.SHAPE_13B, True, 61, label="13b")
+
+
+def test_bf16_hidden_8192_tp_share_two_samples(ctx):
+    # the 70B / 140B hidden size of Table 1 at a TP=8 share, two samples of 2048 tokens
+    s = I.SHAPE_70B_TP8
+    check_layer(ctx, I.LayerShape(s.hidden, s.n_heads, s.head_dim, s.ffn, 2048, 2), True, 62, label="h8192-tp8")
+
+
 # ------------------------------------------------------------- determinism
 def test_two_runs_are_bit_identical(ctx):
     s = I.LayerShape(256, 2, 128, 320, 200, 2)
