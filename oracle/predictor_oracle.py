@@ -1,0 +1,106 @@
+"""Test infrastructure only: a plain Python model of what the workload simulator of Section 3.2 computes
+for one pipeline, written from the definitions so that it can be checked by eye.  Nothing in the
+product imports this file.
+
+The paper states what the simulator returns (time of one iteration step and the maximum memory use of a
+strategy, Section 3.2), the pipeline discipline (PipeDream-1F1B data constraints, Section 3.3), the
+metrics (Eq. 1 throughput, Eq. 2 MFU, Eq. 3 point-to-point volume) and how the "theoretical" figure of a
+mixed cluster is formed (the mean over all accelerators, Section 4.3).  It does not give the simulator's
+inner model; the reading taken here is the textbook one:
+
+* a stage runs its operations one at a time in the 1F1B order: forward of micro-batches 0 .. w-1
+  (w = min(M, P - p) for stage p of P), then backward of m followed by forward of m + w, and the remaining
+  backwards;
+* forward of micro-batch m on stage p starts when the stage is free and the forward of m on stage p-1 has
+  finished and its boundary tensor (Eq. 3 bytes) has crossed the link; backward likewise from stage p+1;
+* the iteration ends when every stage has finished its last backward.
+
+All times in milliseconds, sizes in bytes, link speed in bytes per millisecond.
+"""
+from __future__ import annotations
+
+
+def one_f_one_b_order(p: int, n_stages: int, n_micro: int):
+    """Operation list of stage p: ('F', m) / ('B', m) in execution order (Section 2.3, 1F1B)."""
+    w = min(n_micro, n_stages - p)
+    ops = [("F", m) for m in range(w)]
+    for m in range(n_micro):
+        ops.append(("B", m))
+        if m + w < n_micro:
+            ops.append(("F", m + w))
+    return ops
+
+
+def simulate(fwd_ms, bwd_ms, link_ms, n_micro):
+    """fwd_ms[p], bwd_ms[p]: time of one micro-batch on stage p (all its layers); link_ms[p]: transfer time of
+    one boundary tensor between stage p and p+1 (len P-1).  Returns (iteration_ms, busy_ms[p], finish[p])."""
+    P = len(fwd_ms)
+    orders = [one_f_one_b_order(p, P, n_micro) for p in range(P)]
+    done = {}                       # (kind, p, m) -> finish time
+    nxt = [0] * P                   # next operation index per stage
+    free = [0.0] * P                # time the stage becomes free
+    remaining = sum(len(o) for o in orders)
+    while remaining:
+        progressed = False
+        for p in range(P):
+            while nxt[p] < len(orders[p]):
+                kind, m = orders[p][nxt[p]]
+                if kind == "F":
+                    dep = None if p == 0 else ("F", p - 1, m)
+                    lat = 0.0 if p == 0 else link_ms[p - 1]
+                    dur = fwd_ms[p]
+                else:
+                    dep = None if p == P - 1 else ("B", p + 1, m)
+                    lat = 0.0 if p == P - 1 else link_ms[p]
+                    dur = bwd_ms[p]
+                if dep is not None and dep not in done:
+                    break
+                ready = 0.0 if dep is None else done[dep] + lat
+                start = max(free[p], ready)
+                free[p] = start + dur
+                done[(kind, p, m)] = free[p]
+                nxt[p] += 1
+                remaining -= 1
+                progressed = True
+        if not progressed:
+            raise RuntimeError("schedule deadlocked")
+    busy = [n_micro * (fwd_ms[p] + bwd_ms[p]) for p in range(P)]
+    return max(free), busy, list(free)
+
+
+def live_micro_batches(p: int, n_stages: int, n_micro: int) -> int:
+    """Largest number of micro-batches whose activations stage p holds at once under 1F1B."""
+    live = peak = 0
+    for kind, _ in one_f_one_b_order(p, n_stages, n_micro):
+        live += 1 if kind == "F" else -1
+        peak = max(peak, live)
+    return peak
+
+
+def stage_peak_bytes(p, n_stages, n_micro, n_layers, weight_bytes, grad_bytes, optimizer_bytes, saved_act_bytes):
+    """Parameters, gradients and optimizer state of the stage's layers plus the activations of the live
+    micro-batches (per layer figures as in the per-layer profile record)."""
+    return n_layers * (weight_bytes + grad_bytes + optimizer_bytes) + \
+        live_micro_batches(p, n_stages, n_micro) * n_layers * saved_act_bytes
+
+
+def p2p_bytes(batch, seq, hidden):
+    """Eq. (3): one 16-bit boundary tensor."""
+    return batch * seq * hidden * 2
+
+
+def tgs(seq, global_batch, n_devices, iter_s):
+    """Eq. (1): tokens per device per second."""
+    return seq * global_batch / (n_devices * iter_s)
+
+
+def weighted_mean(values, counts):
+    """Section 4.3: the theoretical figure of a mixed cluster is the mean over all its accelerators."""
+    return sum(v * c for v, c in zip(values, counts)) / sum(counts)
+
+
+def mfu(model_flop_per_iteration, iter_s, peaks_tflops, counts):
+    """Eq. (2): achieved TFLOP/s per device over the mean peak of the cluster's devices."""
+    n = sum(counts)
+    achieved = model_flop_per_iteration / iter_s / n / 1e12
+    return achieved / weighted_mean(peaks_tflops, counts)
