@@ -29,7 +29,7 @@ HH_BF16 = 1
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
            "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
-           "hh_trace_end")
+           "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers")
 TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
 
@@ -56,6 +56,19 @@ class hh_profile_rec(C.Structure):
 
 class hh_trace_sum(C.Structure):
     _fields_ = [("kind", C.c_int32), ("launches", C.c_int32), ("ms", C.c_double), ("work", C.c_double)]
+
+
+class hh_sim_stage(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_devices", C.c_int32), ("fwd_ms", C.c_double), ("bwd_ms", C.c_double),
+                ("peak_tflops", C.c_double), ("link_gbytes_per_s", C.c_double), ("weight_bytes", C.c_uint64),
+                ("grad_bytes", C.c_uint64), ("optimizer_bytes", C.c_uint64), ("saved_act_bytes", C.c_uint64),
+                ("memory_bytes", C.c_uint64)]
+
+
+class hh_sim_result(C.Structure):
+    _fields_ = [("iter_ms", C.c_double), ("bubble_fraction", C.c_double), ("tokens_per_s_per_device", C.c_double),
+                ("tflops_per_device", C.c_double), ("mean_peak_tflops", C.c_double), ("mfu", C.c_double),
+                ("n_devices", C.c_int64)]
 
 
 class HHError(RuntimeError):
@@ -88,6 +101,11 @@ def _load() -> C.CDLL:
         "hh_layer_profile": [vp, cfgp, i, wp, gp, vp, vp, i, i, vp, vp, C.POINTER(hh_profile_rec), vp],
         "hh_trace_begin": [vp, i, C.c_uint32],
         "hh_trace_end": [vp, C.POINTER(hh_trace_sum), i],
+        "hh_sim_pipeline": [C.POINTER(hh_sim_stage), i, i, i, i, i, i, C.c_double, C.POINTER(hh_sim_result), C.POINTER(C.c_double),
+                            C.POINTER(C.c_uint64)],
+        "hh_sim_weighted_mean": [C.POINTER(C.c_double), C.POINTER(C.c_int64), i, C.POINTER(C.c_double)],
+        "hh_plan_layers": [C.POINTER(hh_sim_stage), i, i, i, i, i, i, i, C.c_double, i, C.POINTER(C.c_int32),
+                           C.POINTER(hh_sim_result)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -217,3 +235,37 @@ def hh_trace_end(ctx) -> dict:
     out = (hh_trace_sum * len(TRACE_KINDS))()
     _check(lib.hh_trace_end(ctx, out, len(TRACE_KINDS)))
     return {TRACE_KINDS[r.kind]: (r.launches, r.ms, r.work) for r in out}
+
+
+# ---------------------------------------------------------------- predictor (host only)
+def hh_sim_pipeline(stages: Sequence[hh_sim_stage], n_micro, micro_batch, seq, hidden, data_parallel, flop_per_layer):
+    """-> (hh_sim_result, finish_ms per stage, peak bytes per stage)"""
+    n = len(stages)
+    arr = (hh_sim_stage * max(n, 1))(*stages)
+    res = hh_sim_result()
+    fin = (C.c_double * max(n, 1))()
+    peak = (C.c_uint64 * max(n, 1))()
+    _check(lib.hh_sim_pipeline(arr, n, n_micro, micro_batch, seq, hidden, data_parallel, float(flop_per_layer), C.byref(res), fin,
+                               peak))
+    return res, list(fin)[:n], list(peak)[:n]
+
+
+def hh_sim_weighted_mean(values, counts) -> float:
+    n = len(values)
+    v = (C.c_double * max(n, 1))(*values)
+    c = (C.c_int64 * max(n, 1))(*[int(t) for t in counts])
+    out = C.c_double()
+    _check(lib.hh_sim_weighted_mean(v, c, n, C.byref(out)))
+    return out.value
+
+
+def hh_plan_layers(stages: Sequence[hh_sim_stage], total_layers, n_micro, micro_batch, seq, hidden, data_parallel,
+                   flop_per_layer, slack=2):
+    """-> (layers per stage, hh_sim_result of that split)"""
+    n = len(stages)
+    arr = (hh_sim_stage * max(n, 1))(*stages)
+    out = (C.c_int32 * max(n, 1))()
+    res = hh_sim_result()
+    _check(lib.hh_plan_layers(arr, n, total_layers, n_micro, micro_batch, seq, hidden, data_parallel, float(flop_per_layer), slack,
+                              out, C.byref(res)))
+    return list(out)[:n], res

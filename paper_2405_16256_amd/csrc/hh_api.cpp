@@ -60,6 +60,10 @@ static int hip_fail(hipError_t e, const char* what) {
     } while (0)
 
 extern "C" const char* hh_last_error(void) { return g_err; }
+namespace hh {
+// for the other translation units of the library
+int set_error(int code, const char* msg) { return fail(code, "%s", msg); }
+}  // namespace hh
 
 // ------------------------------------------------------------------ context
 struct TraceRec {

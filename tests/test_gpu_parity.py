@@ -451,3 +451,32 @@ def test_trace_counts_launches_per_family_and_honours_the_mask(ctx):
     hh.hh_trace_begin(ctx, 1, ["attn_fwd"])
     fam = hh.hh_trace_end(ctx)
     assert all(v[0] == 0 for v in fam.values())
+
+
+def test_profile_records_feed_the_pipeline_predictor(ctx):
+    """Section 3.2: the per-layer times measured on this accelerator (and a second, hypothetical type that is 1.5x
+    slower) drive the simulator and the layer split."""
+    s = I.LayerShape(512, 4, 128, 1024, 512, 2)
+    cfg = L.cfg_of(s, True)
+    layer = L.DeviceLayer(I.layer_weights(53, 0, s, True), s, True)
+    x_np, dy_np = I.activations(53, s, 0, True)
+    x, dy = L.to_dev(x_np, True), L.to_dev(dy_np, True)
+    pool_b, wsb = hh.hh_stage_sizes(cfg, 1, 1)
+    pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
+    wsp = torch.empty(wsb, dtype=torch.uint8, device=L.DEV)
+    rec = hh.hh_layer_profile(ctx, cfg, [layer.wstruct], [layer.gstruct], x, dy, 2, 5, pool, wsp, L.stream_ptr())[0]
+
+    def stage_of(slow):
+        return hh.hh_sim_stage(0, 8, rec.fwd_ms * slow, rec.bwd_ms * slow, 2500.0 / slow, 25.0, rec.weight_bytes, rec.grad_bytes,
+                               3 * rec.grad_bytes, rec.saved_act_bytes, 0)
+
+    stages = [stage_of(1.0), stage_of(1.0), stage_of(1.5), stage_of(1.5)]
+    layers, res = hh.hh_plan_layers(stages, 40, 16, s.micro_batch, s.seq, s.hidden, 1, rec.fwd_flop + rec.bwd_flop)
+    assert sum(layers) == 40 and layers[0] > layers[2] and layers[1] > layers[3]
+    for st, n in zip(stages, layers):
+        st.n_layers = n
+    again, fin, peak = hh.hh_sim_pipeline(stages, 16, s.micro_batch, s.seq, s.hidden, 1, rec.fwd_flop + rec.bwd_flop)
+    assert again.iter_ms == res.iter_ms and max(fin) == res.iter_ms
+    assert peak[0] == layers[0] * (rec.weight_bytes + 4 * rec.grad_bytes) + 4 * layers[0] * rec.saved_act_bytes
+    assert 0.0 < res.mfu < 1.0 and res.tokens_per_s_per_device > 0
+    say("  planned layers %s, iteration %.2f ms, MFU %.3f of a mean peak of %.0f TFLOP/s" % (layers, res.iter_ms, res.mfu, res.mean_peak_tflops))
