@@ -330,6 +330,11 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
     const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds0 + wave * 4096);
 
+    constexpr uint32_t CES = OUT_F32 ? 4u : 2u;
+    constexpr uint32_t OUT_OF_RANGE = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t rsC = make_rsrc(Cv, (uint32_t)(((size_t)(M - 1) * ldc + N) * CES));
+    const __amdgpu_buffer_rsrc_t rsR = make_rsrc(R ? (const void*)R : (const void*)Cv, R ? (uint32_t)(((size_t)(M - 1) * ldr + N) * 2u) : 0u);
+
 #define SB() __builtin_amdgcn_sched_barrier(0)
     // one DMA instruction of the k tile being issued (i < 4: A part i, else B part i-4) into stage st
     auto dma_part = [&](int st, int i) {
@@ -448,69 +453,61 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
             fresh = false;
         }
 
-        // epilogue: lane owns row m = .. + (lane & 31); register 4g+e holds column n = .. + 8g + 4(lane>>5) + e.
-        // What has to be read (old fp32 sums, or the bf16 residual) is fetched for a whole row block in one
-        // batch of branch-free loads -- invalid lanes read the tile's first element -- before anything is stored.
+        // Epilogue.  In the accumulators a lane owns one row and 4-column pieces of it, which would make every
+        // store instruction touch 32 rows with 16 or 32 bytes each.  Each 32x32 block therefore goes through a
+        // wave-private 4 KB LDS patch (fp32, 16-byte chunks XOR-swizzled by the row) and comes back with 8
+        // lanes per row: loads of what is added (old fp32 sums or the bf16 residual) and stores then cover
+        // whole 128-byte (fp32) or 64-byte (bf16) row segments.  C and R are reached through bounds-checked
+        // buffers: rows past M fall behind the buffer's end, columns past N get an out-of-range offset.
+        {
+            char* const patch = smem + DSTAGES * 2 * DSTAGE_BYTES + wave * 4096;
+            const int r_w = lane & 31;                       // row written, chunks 2g + hf
+            const int r_r = lane >> 3, c_r = lane & 7;       // row (+ 8t) and chunk read back
 #pragma unroll
-        for (int i = 0; i < TM; i++) {
-            const int m = cm0 + wm + 32 * i + (lane & 31);
-            bool valid[TN][4];
-            int n_of[TN][4];
+            for (int i = 0; i < TM; i++) {
+                const uint32_t row_base = (uint32_t)(cm0 + wm + 32 * i + r_r);
+                float4 add[TN][4];
+                uint32_t off_c[TN][4];
 #pragma unroll
-            for (int j = 0; j < TN; j++)
+                for (int j = 0; j < TN; j++) {
+                    const int col = cn0 + wn + 32 * j + 4 * c_r;
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    n_of[j][g] = cn0 + wn + 32 * j + 8 * g + 4 * hf;
-                    valid[j][g] = m < M && n_of[j][g] < N;
-                }
-            if (OUT_F32) {
-                float* Cf = reinterpret_cast<float*>(Cv);
-                float4 old[TN][4];
-                if (cacc) {
-#pragma unroll
-                    for (int j = 0; j < TN; j++)
-#pragma unroll
-                        for (int g = 0; g < 4; g++) {
-                            const size_t at = valid[j][g] ? (size_t)m * ldc + n_of[j][g] : (size_t)cm0 * ldc + cn0;
-                            old[j][g] = *reinterpret_cast<const float4*>(Cf + at);
+                    for (int t = 0; t < 4; t++) {
+                        const uint32_t row = row_base + 8 * t;
+                        off_c[j][t] = col < N ? (row * (uint32_t)ldc + (uint32_t)col) * CES : OUT_OF_RANGE;
+                        add[j][t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (OUT_F32) {
+                            if (cacc) {
+                                const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsC, off_c[j][t], 0, 0);
+                                add[j][t] = make_float4(__int_as_float(v[0]), __int_as_float(v[1]), __int_as_float(v[2]), __int_as_float(v[3]));
+                            }
+                        } else if (R) {
+                            const uint32_t off_r = col < N ? (row * (uint32_t)ldr + (uint32_t)col) * 2u : OUT_OF_RANGE;
+                            const i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsR, off_r, 0, 0);
+                            add[j][t] = make_float4(lo_bf((uint32_t)v[0]), hi_bf((uint32_t)v[0]), lo_bf((uint32_t)v[1]), hi_bf((uint32_t)v[1]));
                         }
-                }
-#pragma unroll
-                for (int j = 0; j < TN; j++)
-#pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                        if (cacc) { v.x += old[j][g].x; v.y += old[j][g].y; v.z += old[j][g].z; v.w += old[j][g].w; }
-                        if (valid[j][g]) *reinterpret_cast<float4*>(Cf + (size_t)m * ldc + n_of[j][g]) = v;
                     }
-            } else {
-                bf16_t* Cb = reinterpret_cast<bf16_t*>(Cv);
-                uint2 res[TN][4];
-                if (R) {
-#pragma unroll
-                    for (int j = 0; j < TN; j++)
-#pragma unroll
-                        for (int g = 0; g < 4; g++) {
-                            const size_t at = valid[j][g] ? (size_t)m * ldr + n_of[j][g] : (size_t)cm0 * ldr + cn0;
-                            res[j][g] = *reinterpret_cast<const uint2*>(R + at);
-                        }
                 }
 #pragma unroll
-                for (int j = 0; j < TN; j++)
+                for (int j = 0; j < TN; j++) {
 #pragma unroll
-                    for (int g = 0; g < 4; g++) {
-                        float v[4];
+                    for (int g = 0; g < 4; g++)
+                        *reinterpret_cast<float4*>(patch + r_w * 128 + (((2 * g + hf) ^ ((r_w >> 1) & 7)) << 4)) =
+                            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
 #pragma unroll
-                        for (int e = 0; e < 4; e++) v[e] = acc[i][j][4 * g + e];
-                        if (R) {
-                            v[0] += lo_bf(res[j][g].x); v[1] += hi_bf(res[j][g].x);
-                            v[2] += lo_bf(res[j][g].y); v[3] += hi_bf(res[j][g].y);
+                    for (int t = 0; t < 4; t++) {
+                        const int rr = 8 * t + r_r;
+                        float4 v = *reinterpret_cast<const float4*>(patch + rr * 128 + ((c_r ^ ((rr >> 1) & 7)) << 4));
+                        v.x += add[j][t].x; v.y += add[j][t].y; v.z += add[j][t].z; v.w += add[j][t].w;
+                        if (OUT_F32) {
+                            const i32x4 o = {__float_as_int(v.x), __float_as_int(v.y), __float_as_int(v.z), __float_as_int(v.w)};
+                            __builtin_amdgcn_raw_buffer_store_b128(o, rsC, off_c[j][t], 0, 0);
+                        } else {
+                            const i32x2 o = {(int)pack_bf2(v.x, v.y), (int)pack_bf2(v.z, v.w)};
+                            __builtin_amdgcn_raw_buffer_store_b64(o, rsC, off_c[j][t], 0, 0);
                         }
-                        uint2 o;
-                        o.x = pack_bf2(v[0], v[1]);
-                        o.y = pack_bf2(v[2], v[3]);
-                        if (valid[j][g]) *reinterpret_cast<uint2*>(Cb + (size_t)m * ldc + n_of[j][g]) = o;
                     }
+                }
             }
         }
         if (!has_next) return;
@@ -563,7 +560,7 @@ constexpr int NUM_CU = 256;
 // summed in a fixed order by a small second kernel).
 template <int KIND, bool OUT_F32>
 static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
-    constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES;
+    constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES + 8 * 4096;   // two stages + the epilogue patches of the 8 waves
     static bool attr_set = false;
     auto kern = k_gemm_dma<KIND, OUT_F32>;
     if (!attr_set) {
@@ -611,6 +608,9 @@ hipError_t gemm_bf16(const GemmDesc& g, hipStream_t st) {
     const long a_bytes = ((a_rows - 1) * g.lda + a_cols) * 2, b_bytes = ((b_rows - 1) * g.ldb + b_cols) * 2;
     if (a_bytes >= (1L << 32) - (1L << 25) || b_bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
     if (g.lda > 65535 || g.ldb > 65535) return hipErrorInvalidValue;
+    // C (and the residual) are addressed with 32-bit byte offsets below 2 GB
+    if (((long)(g.M - 1) * g.ldc + g.N) * (g.out_f32 ? 4 : 2) >= (1L << 31)) return hipErrorInvalidValue;
+    if (g.R && ((long)(g.M - 1) * g.ldr + g.N) * 2 >= (1L << 31)) return hipErrorInvalidValue;
     // a k-contiguous operand is fetched 64 k values at a time with no per-row bound
     if (g.kind != GEMM_TN && g.K % 64 != 0) return hipErrorInvalidValue;
     // activations come out in bf16 (NT, NN), parameter gradients in fp32 (TN)
