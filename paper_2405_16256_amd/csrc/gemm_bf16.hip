@@ -296,9 +296,6 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
                                                   int block0, int block_end, int ksplit, float* __restrict__ partial) {
     // ksplit == 1: the workgroup walks tiles block0 + blockIdx.x, + gridDim.x, ... < block_end over the whole
     //   k range; the first DMA stages of the next tile are issued before the epilogue of the current one.
-    //   For fp32 "+=" outputs every second group of 8 workgroups cuts its FIRST tile into two k halves
-    //   (two read-modify-write epilogues): from then on its epilogues fall half a tile period after the
-    //   others', so the chip's 128 MB read+write bursts overlap the other half's MFMA phase.
     // ksplit  > 1: workgroup blockIdx.x computes tile (block0 + blockIdx.x / ksplit) over the
     //   (blockIdx.x % ksplit)-th share of the k range and writes fp32 sums to partial[blockIdx.x][256][256].
     constexpr bool A_KC = (KIND != GEMM_TN);
@@ -315,12 +312,8 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
     const int nk_all = (K + DK - 1) / DK;
-    int kbeg = (int)((long)chunk * nk_all / ksplit), kend = (int)((long)(chunk + 1) * nk_all / ksplit);
-    int nk = kend - kbeg;
-    int acc_now = accumulate;
-    // 0: whole tiles; 1: first half of the first tile is running; 2: its second half is running
-    int skew = (OUT_F32 && ksplit == 1 && ((blockIdx.x >> 3) & 1) && tix + (int)gridDim.x < block_end && nk_all >= 8) ? 1 : 0;
-    if (skew) { kend = nk_all / 2; nk = kend; }
+    const int kbeg = (int)((long)chunk * nk_all / ksplit), kend = (int)((long)(chunk + 1) * nk_all / ksplit);
+    const int nk = kend - kbeg;
 
     const uint64_t pa = (uint64_t)A, pb = (uint64_t)B;
     const i32x4 rsA = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)a_bytes, 0x00020000};
@@ -437,17 +430,12 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
         }
 
         // next piece of work of this workgroup: start its loads before writing this one out
-        const int cm0 = m0, cn0 = n0, cacc = acc_now;
-        bool has_next;
-        if (skew == 1) {          // same tile, second k half, added to what the first half wrote
-            skew = 2; kbeg = kend; kend = nk_all; nk = kend - kbeg; acc_now = 1; has_next = true;
-        } else {
-            if (skew == 2) { skew = 0; kbeg = 0; kend = nk_all; nk = nk_all; acc_now = accumulate; }
-            tix += stride;
-            has_next = tix < block_end;
-            if (has_next) { tile_of_index(tix, tiles_m, tiles_n, tm, tn); m0 = tm * DTILE; n0 = tn * DTILE; }
-        }
+        const int cm0 = m0, cn0 = n0, cacc = accumulate;
+        tix += stride;
+        const bool has_next = tix < block_end;
         if (has_next) {
+            tile_of_index(tix, tiles_m, tiles_n, tm, tn);
+            m0 = tm * DTILE; n0 = tn * DTILE;
             __syncthreads();   // every wave has finished reading the LDS stages
             start_tile(m0, n0);
             fresh = false;
