@@ -146,11 +146,16 @@ __device__ __forceinline__ void load_qfrag(bf16x8 (&f)[D / 16], __amdgpu_buffer_
 }
 
 // ------------------------------------------------------------------ forward
-template <int D>
-__global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+// NPAR = 1: 4 waves, each 32 queries of the block's 128, walking the key tiles one by one.
+// NPAR = 2: 8 waves; waves 4..7 repeat the queries of waves 0..3 and the two groups take the even and the odd
+//   key tiles (two tiles per step), so the longest job of the launch -- the last query block -- is half as
+//   long and the two waves of a SIMD overlap each other's MFMA and softmax phases.  The two partial results
+//   (accumulator, running maximum, sum) are merged through LDS at the end, always in the same order.
+template <int D, int NPAR>
+__global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                        bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh, int B) {
     using TL = Tile<D>;
-    constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
+    constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
     extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
     // flattened grid, last query block first: the long jobs of every head and sample are dispatched
     // before the short ones
@@ -158,16 +163,22 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restri
     const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
-    const int q0 = qb * 128 + wave * 32;
+    const int wq = wave & 3, par = wave >> 2;
+    const int q0 = qb * 128 + wq * 32;
     const int query = q0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
     const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const typename TL::Offsets offs = TL::offsets();
-    auto issue = [&](int st, int kv) {
-        TL::dma(lds0 + st * STAGE, rsw, tokb + kv, ld, A + h * D);
-        TL::dma(lds0 + st * STAGE + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+    // step s brings key tiles NPAR*s .. NPAR*s + NPAR-1
+    auto issue = [&](int st, int s) {
+#pragma unroll
+        for (int p = 0; p < NPAR; p++) {
+            const uint32_t kv = (uint32_t)(NPAR * s + p) * 64u;
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, A + h * D);
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+        }
     };
     issue(0, 0);
 
@@ -183,12 +194,12 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restri
     const float c = LOG2E / sqrtf((float)D);
 
     const int q_last = min(qb * 128 + 127, S - 1);
-    int t = 0;
-    for (int kv0 = 0; kv0 <= q_last; kv0 += 64, t++) {
+    for (int s = 0; s * (64 * NPAR) <= q_last; s++) {
         wait_dma();
-        __syncthreads();   // tile t is in LDS for everyone; everyone has finished with tile t-1
-        if (kv0 + 64 <= q_last) issue((t + 1) & 1, kv0 + 64);
-        const char* sK = smem + (t & 1) * STAGE;
+        __syncthreads();   // the tiles of step s are in LDS for everyone; everyone has finished with step s-1
+        if ((s + 1) * (64 * NPAR) <= q_last) issue((s + 1) & 1, s + 1);
+        const int kv0 = (NPAR * s + par) * 64;
+        const char* sK = smem + (s & 1) * STAGE + par * 2 * TL::BYTES;
         const char* sV = sK + TL::BYTES;
         if (kv0 > q0 + 31) continue;  // every key of the tile lies after every query of this wave
         f32x16 sacc[2];
@@ -250,6 +261,30 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_fwd(const bf16_t* __restri
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[kk], oacc[dt], 0, 0, 0);
             });
     }
+    if (NPAR == 2) {
+        // merge the odd-tile group into the even-tile group: [query wave][register][lane] floats, then m and the sum
+        __syncthreads();   // nobody reads a K/V tile any more and no DMA is in flight
+        float* mo = reinterpret_cast<float*>(smem) + wq * ((D / 2 + 2) * WAVE);
+        if (par == 1) {
+#pragma unroll
+            for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) mo[(dt * 16 + r) * WAVE + lane] = oacc[dt][r];
+            mo[(D / 2) * WAVE + lane] = m;
+            mo[(D / 2 + 1) * WAVE + lane] = lsum;
+        }
+        __syncthreads();
+        if (par == 1) return;
+        const float m1 = mo[(D / 2) * WAVE + lane], l1 = mo[(D / 2 + 1) * WAVE + lane];
+        const float mn = fmaxf(m, m1);
+        const float a0 = __builtin_amdgcn_exp2f(m - mn), a1 = __builtin_amdgcn_exp2f(m1 - mn);   // a group without tiles has m = -inf, sum 0
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) oacc[dt][r] = oacc[dt][r] * a0 + mo[(dt * 16 + r) * WAVE + lane] * a1;
+        lsum = lsum * a0 + l1 * a1;
+        m = mn;
+    }
     lsum += __shfl_xor(lsum, 32, WAVE);
     if (query < S) {
         const float inv = 1.0f / lsum;
@@ -291,19 +326,22 @@ __global__ __launch_bounds__(ATHREADS) void k_attn_delta(const bf16_t* __restric
 }
 
 // --------------------------------------------------------------- backward: dQ
-template <int D>
-__global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+// NPAR as in k_attn_fwd: with 2, the even and the odd key tiles go to two groups of 4 waves whose dQ sums
+// are added through LDS at the end.
+template <int D, int NPAR>
+__global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                           const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                           const float* __restrict__ lse, const float* __restrict__ dvec,
                                                           bf16_t* __restrict__ dqkv, int S, int nh, int B) {
     using TL = Tile<D>;
-    constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
+    constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
     extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
     const int nhb = nh * B;   // flattened grid, last query block first (see k_attn_fwd)
     const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
-    const int q0 = qb * 128 + wave * 32;
+    const int wq = wave & 3, par = wave >> 2;
+    const int q0 = qb * 128 + wq * 32;
     const int query = q0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
@@ -311,9 +349,13 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __res
     const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const typename TL::Offsets offs = TL::offsets();
-    auto issue = [&](int st, int kv) {
-        TL::dma(lds0 + st * STAGE, rsw, tokb + kv, ld, A + h * D);
-        TL::dma(lds0 + st * STAGE + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+    auto issue = [&](int st, int s) {
+#pragma unroll
+        for (int p = 0; p < NPAR; p++) {
+            const uint32_t kv = (uint32_t)(NPAR * s + p) * 64u;
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, A + h * D);
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+        }
     };
     issue(0, 0);
 
@@ -334,12 +376,12 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __res
         for (int r = 0; r < 16; r++) dq[i][r] = 0.f;
 
     const int q_last = min(qb * 128 + 127, S - 1);
-    int t = 0;
-    for (int kv0 = 0; kv0 <= q_last; kv0 += 64, t++) {
+    for (int s = 0; s * (64 * NPAR) <= q_last; s++) {
         wait_dma();
-        __syncthreads();   // tile t is in LDS for everyone; everyone has finished with tile t-1
-        if (kv0 + 64 <= q_last) issue((t + 1) & 1, kv0 + 64);
-        const char* sK = smem + (t & 1) * STAGE;
+        __syncthreads();   // the tiles of step s are in LDS for everyone; everyone has finished with step s-1
+        if ((s + 1) * (64 * NPAR) <= q_last) issue((s + 1) & 1, s + 1);
+        const int kv0 = (NPAR * s + par) * 64;
+        const char* sK = smem + (s & 1) * STAGE + par * 2 * TL::BYTES;
         const char* sV = sK + TL::BYTES;
         if (kv0 > q0 + 31) continue;
         f32x16 sacc[2], pacc[2];
@@ -374,6 +416,22 @@ __global__ __launch_bounds__(ATHREADS, 2) void k_attn_bwd_dq(const bf16_t* __res
                 const int kk = idx / (D / 32), dt = idx % (D / 32);
                 dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk], dq[dt], 0, 0, 0);
             });
+    }
+    if (NPAR == 2) {
+        __syncthreads();   // nobody reads a K/V tile any more and no DMA is in flight
+        float* mo = reinterpret_cast<float*>(smem) + wq * ((D / 2) * WAVE);
+        if (par == 1) {
+#pragma unroll
+            for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) mo[(dt * 16 + r) * WAVE + lane] = dq[dt][r];
+        }
+        __syncthreads();
+        if (par == 1) return;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) dq[dt][r] += mo[(dt * 16 + r) * WAVE + lane];
     }
     if (query < S) {
         bf16_t* row = dqkv + (size_t)(tokb + query) * ld + h * D;
@@ -566,31 +624,51 @@ static hipError_t set_lds(K kern, int bytes) {
     return bytes > 48 * 1024 ? hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) : hipSuccess;
 }
 
+// Key tiles are split between two wave groups (NPAR = 2) when the launch is bound by its longest job: few enough
+// workgroups that all of them run at once, i.e. no later jobs to fill the CUs that the short ones leave.
+static bool split_keys(unsigned grid, int S) { return S >= 1024 && grid <= 2 * 256; }
+
 template <int D>
 static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float* lse, int B, int S, int nh, hipStream_t st) {
-    constexpr int LDS = 4 * Tile<D>::BYTES;
-    hipError_t e = set_lds(k_attn_fwd<D>, LDS);
-    if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
-    k_attn_fwd<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, B);
+    if (split_keys(grid, S)) {
+        constexpr int LDS = 8 * Tile<D>::BYTES;
+        hipError_t e = set_lds(k_attn_fwd<D, 2>, LDS);
+        if (e != hipSuccess) return e;
+        k_attn_fwd<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, B);
+    } else {
+        constexpr int LDS = 4 * Tile<D>::BYTES;
+        hipError_t e = set_lds(k_attn_fwd<D, 1>, LDS);
+        if (e != hipSuccess) return e;
+        k_attn_fwd<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, B);
+    }
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, const void* dout, uint32_t do_bytes,
                         const float* lse, float* dvec, void* dqkv, int B, int S, int nh, hipStream_t st) {
-    constexpr int LDS = 4 * Tile<D>::BYTES, LDS_KV = 8 * Tile<D>::BYTES + 1024;
-    hipError_t e = set_lds(k_attn_bwd_dq<D>, LDS);
-    if (e != hipSuccess) return e;
-    e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
+    constexpr int LDS_KV = 8 * Tile<D>::BYTES + 1024;
+    hipError_t e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
     const long rows = (long)B * S * nh;
     k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
-    k_attn_bwd_dq<D><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                  (bf16_t*)dqkv, S, nh, B);
+    if (split_keys(grid, S)) {
+        constexpr int LDS = 8 * Tile<D>::BYTES;
+        e = set_lds(k_attn_bwd_dq<D, 2>, LDS);
+        if (e != hipSuccess) return e;
+        k_attn_bwd_dq<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+                                                             (bf16_t*)dqkv, S, nh, B);
+    } else {
+        constexpr int LDS = 4 * Tile<D>::BYTES;
+        e = set_lds(k_attn_bwd_dq<D, 1>, LDS);
+        if (e != hipSuccess) return e;
+        k_attn_bwd_dq<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+                                                         (bf16_t*)dqkv, S, nh, B);
+    }
     k_attn_bwd_dkv<D><<<grid, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
-                                                                         dvec, (bf16_t*)dqkv, S, nh, B);
+                                                       dvec, (bf16_t*)dqkv, S, nh, B);
     return hipGetLastError();
 }
 

@@ -112,6 +112,12 @@ def test_bf16_140b_class_tp_share_full_size(ctx):
     check_layer(ctx, I.CFG3, True, I.SEEDS["cfg3"], label="cfg3")
 
 
+def test_bf16_head_dim_64_long_ragged_sequence(ctx):
+    # S = 1100 (ragged) with few workgroups: attention forward and dQ run with the key tiles split between two
+    # wave groups, here for head_dim 64
+    check_layer(ctx, I.LayerShape(512, 8, 64, 1024, 1100, 1), True, 63, label="d64-long")
+
+
 def test_bf16_13b_class_layer_full_size(ctx):
     # hidden 5120 (Table 1): 20 x 20 tiles of 256 leave k-split tails in every GEMM family
     check_layer(ctx, I.SHAPE_13B, True, 61, label="13b")
