@@ -94,31 +94,35 @@ def causal_probs(qh, kh):
 
 
 def attention_forward(q, k, v):
-    """q,k,v: [B,S,nh,d] -> o [B,S,nh,d]; one causal softmax per (sample, head)."""
+    """q: [B,S,nh,d]; k,v: [B,S,nkv,d] with nh a multiple of nkv -> o [B,S,nh,d].  One causal softmax per
+    (sample, query head); query head h reads key/value head h // (nh // nkv) (grouped-query attention;
+    nkv == nh is the ordinary multi-head case)."""
     B, S, nh, d = q.shape
+    G = nh // k.shape[2]
     o = np.empty_like(q)
     for b in range(B):
         for h in range(nh):
-            P = causal_probs(q[b, :, h], k[b, :, h])
-            o[b, :, h] = P @ v[b, :, h]
+            P = causal_probs(q[b, :, h], k[b, :, h // G])
+            o[b, :, h] = P @ v[b, :, h // G]
     return o
 
 
 def attention_backward(do, q, k, v):
-    """Gradients of attention_forward wrt q, k, v."""
+    """Gradients of attention_forward wrt q, k, v; a key/value head collects the gradients of its G query heads."""
     B, S, nh, d = q.shape
-    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    G = nh // k.shape[2]
+    dq, dk, dv = np.empty_like(q), np.zeros_like(k), np.zeros_like(v)
     inv = 1.0 / np.sqrt(F64(d))
     for b in range(B):
         for h in range(nh):
-            qh, kh, vh, doh = q[b, :, h], k[b, :, h], v[b, :, h], do[b, :, h]
+            qh, kh, vh, doh = q[b, :, h], k[b, :, h // G], v[b, :, h // G], do[b, :, h]
             P = causal_probs(qh, kh)
-            dv[b, :, h] = P.T @ doh
+            dv[b, :, h // G] += P.T @ doh
             dP = doh @ vh.T
             D = np.sum(P * dP, axis=1, keepdims=True)
             dZ = P * (dP - D)
             dq[b, :, h] = (dZ @ kh) * inv
-            dk[b, :, h] = (dZ.T @ qh) * inv
+            dk[b, :, h // G] += (dZ.T @ qh) * inv
     return dq, dk, dv
 
 
@@ -140,18 +144,20 @@ def _f64(w):
     return {n: np.asarray(a, dtype=F64) for n, a in w.items()}
 
 
-def layer_forward(x, w, n_heads, head_dim, eps=1e-5, rope_base=10000.0):
-    """One decoder layer.  x: [B,S,H];  w: dict of the 9 parameters.  -> (y, cache)."""
+def layer_forward(x, w, n_heads, head_dim, eps=1e-5, rope_base=10000.0, n_kv_heads=None):
+    """One decoder layer.  x: [B,S,H];  w: dict of the 9 parameters (wk, wv: [n_kv_heads*head_dim, H]).
+    -> (y, cache)."""
     x = np.asarray(x, dtype=F64)
     w = _f64(w)
     B, S, H = x.shape
     nh, d = n_heads, head_dim
+    nkv = nh if n_kv_heads is None else n_kv_heads
     phi = rope_angles(S, d, rope_base)
 
     xn, r1 = rmsnorm_forward(x, w["g_attn"], eps)
     q = (xn @ w["wq"].T).reshape(B, S, nh, d)
-    k = (xn @ w["wk"].T).reshape(B, S, nh, d)
-    v = (xn @ w["wv"].T).reshape(B, S, nh, d)
+    k = (xn @ w["wk"].T).reshape(B, S, nkv, d)
+    v = (xn @ w["wv"].T).reshape(B, S, nkv, d)
     qr = rope_forward(q, phi)
     kr = rope_forward(k, phi)
     o = attention_forward(qr, kr, v)
@@ -165,7 +171,7 @@ def layer_forward(x, w, n_heads, head_dim, eps=1e-5, rope_base=10000.0):
     y = h + m @ w["w_down"].T
 
     cache = dict(x=x, r1=r1, xn=xn, qr=qr, kr=kr, v=v, a=a, h=h, r2=r2, hn=hn,
-                 gt=gt, u=u, m=m, phi=phi, nh=nh, d=d)
+                 gt=gt, u=u, m=m, phi=phi, nh=nh, nkv=nkv, d=d)
     return y, cache
 
 
@@ -175,7 +181,7 @@ def layer_backward(dy, w, cache):
     w = _f64(w)
     c = cache
     B, S, H = dy.shape
-    nh, d = c["nh"], c["d"]
+    nh, nkv, d = c["nh"], c["nkv"], c["d"]
     T = B * S
     flat = lambda t: t.reshape(T, -1)
     g = {}
@@ -195,8 +201,8 @@ def layer_backward(dy, w, cache):
     do = (dh @ w["wo"]).reshape(B, S, nh, d)
     dqr, dkr, dv = attention_backward(do, c["qr"], c["kr"], c["v"])
     dq = rope_backward(dqr, c["phi"]).reshape(B, S, nh * d)
-    dk = rope_backward(dkr, c["phi"]).reshape(B, S, nh * d)
-    dv = dv.reshape(B, S, nh * d)
+    dk = rope_backward(dkr, c["phi"]).reshape(B, S, nkv * d)
+    dv = dv.reshape(B, S, nkv * d)
     g["wq"] = flat(dq).T @ flat(c["xn"])
     g["wk"] = flat(dk).T @ flat(c["xn"])
     g["wv"] = flat(dv).T @ flat(c["xn"])
@@ -207,7 +213,7 @@ def layer_backward(dy, w, cache):
 
 
 # --------------------------------------------------------------- stage step
-def stage_step(xs, dys, ws, n_heads, head_dim, eps=1e-5, rope_base=10000.0):
+def stage_step(xs, dys, ws, n_heads, head_dim, eps=1e-5, rope_base=10000.0, n_kv_heads=None):
     """A pipeline stage of k = len(ws) layers over M = len(xs) micro-batches.
 
     All micro-batches run forward through the k layers (layer l's output feeds
@@ -219,7 +225,7 @@ def stage_step(xs, dys, ws, n_heads, head_dim, eps=1e-5, rope_base=10000.0):
     for m in range(M):
         t, cs = np.asarray(xs[m], dtype=F64), []
         for l in range(k):
-            t, c = layer_forward(t, ws[l], n_heads, head_dim, eps, rope_base)
+            t, c = layer_forward(t, ws[l], n_heads, head_dim, eps, rope_base, n_kv_heads)
             cs.append(c)
         ys.append(t)
         caches.append(cs)

@@ -109,10 +109,19 @@ class LayerShape:
     micro_batch: int = 1
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    n_kv_heads: int = 0          # 0: as many as n_heads (multi-head attention); else a divisor of n_heads
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
 
     @property
     def attn(self) -> int:
         return self.n_heads * self.head_dim
+
+    @property
+    def attn_kv(self) -> int:
+        return self.kv_heads * self.head_dim
 
     @property
     def tokens(self) -> int:
@@ -131,8 +140,8 @@ SEEDS = {"cfg1": 1001, "cfg2": 1002, "cfg3": 1003, "cfg4": 1004, "cfg5": 1005}
 
 
 def weight_shapes(s: LayerShape) -> dict:
-    H, A, F = s.hidden, s.attn, s.ffn
-    return {"g_attn": (H,), "wq": (A, H), "wk": (A, H), "wv": (A, H), "wo": (H, A),
+    H, A, Akv, F = s.hidden, s.attn, s.attn_kv, s.ffn
+    return {"g_attn": (H,), "wq": (A, H), "wk": (Akv, H), "wv": (Akv, H), "wo": (H, A),
             "g_mlp": (H,), "w_gate": (F, H), "w_up": (F, H), "w_down": (H, F)}
 
 

@@ -396,3 +396,58 @@ def test_against_autograd_of_the_same_equations():
     np.testing.assert_allclose(dxo, tx.grad.numpy(), rtol=1e-10, atol=1e-11)
     for n in I.WEIGHT_NAMES:
         np.testing.assert_allclose(g[n], tw[n].grad.numpy(), rtol=1e-10, atol=1e-11, err_msg=n)
+
+
+# ------------------------------------------------------ grouped-query attention
+def test_grouped_query_attention_equals_multi_head_with_repeated_kv_heads():
+    """With key/value heads shared by G query heads the layer must equal the multi-head layer whose wk, wv rows are
+    the shared heads repeated G times, and the gradient of a shared head is the sum over its copies."""
+    H, nh, nkv, d, F, S, B = 24, 6, 2, 4, 20, 7, 2
+    G = nh // nkv
+    s = I.LayerShape(H, nh, d, F, S, B, n_kv_heads=nkv)
+    w = {n: I.normal(11, 200 + p, shp, 0.4, 1.0 if n.startswith("g_") else 0.0).astype(np.float64)
+         for p, (n, shp) in enumerate(I.weight_shapes(s).items())}
+    assert w["wk"].shape == (nkv * d, H) and w["wq"].shape == (nh * d, H)
+    x = I.normal(11, 1, (B, S, H)).astype(np.float64)
+    dy = I.normal(11, 2, (B, S, H)).astype(np.float64)
+    y, cache = O.layer_forward(x, w, nh, d, n_kv_heads=nkv)
+    dx, g = O.layer_backward(dy, w, cache)
+    rep = lambda m: m.reshape(nkv, 1, d, H).repeat(G, axis=1).reshape(nh * d, H)
+    w2 = dict(w, wk=rep(w["wk"]), wv=rep(w["wv"]))
+    y2, cache2 = O.layer_forward(x, w2, nh, d)
+    dx2, g2 = O.layer_backward(dy, w2, cache2)
+    np.testing.assert_allclose(y, y2, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dx, dx2, rtol=1e-11, atol=1e-12)
+    fold = lambda m: m.reshape(nkv, G, d, H).sum(axis=1).reshape(nkv * d, H)
+    np.testing.assert_allclose(g["wk"], fold(g2["wk"]), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(g["wv"], fold(g2["wv"]), rtol=1e-11, atol=1e-12)
+    for n in ("wq", "wo", "g_attn", "g_mlp", "w_gate", "w_up", "w_down"):
+        np.testing.assert_allclose(g[n], g2[n], rtol=1e-11, atol=1e-12)
+    # the grouping is by consecutive query heads: pairing head h with kv head h % nkv instead must differ
+    q = cache["qr"]
+    wrong = np.stack([O.causal_probs(q[0, :, h], cache["kr"][0, :, h % nkv]) @ cache["v"][0, :, h % nkv] for h in range(nh)], axis=1)
+    assert np.abs(wrong.reshape(S, nh * d) - cache["a"][0]).max() > 1e-3
+
+
+def test_grouped_query_layer_finite_differences():
+    H, nh, nkv, d, F, S, B = 12, 4, 1, 4, 10, 5, 1
+    s = I.LayerShape(H, nh, d, F, S, B, n_kv_heads=nkv)
+    w = {n: I.normal(12, 300 + p, shp, 0.4, 1.0 if n.startswith("g_") else 0.0).astype(np.float64)
+         for p, (n, shp) in enumerate(I.weight_shapes(s).items())}
+    x = I.normal(12, 1, (B, S, H)).astype(np.float64)
+    dy = I.normal(12, 2, (B, S, H)).astype(np.float64)
+    y, cache = O.layer_forward(x, w, nh, d, n_kv_heads=nkv)
+    dx, g = O.layer_backward(dy, w, cache)
+    loss = lambda xx, ww: float(np.sum(O.layer_forward(xx, ww, nh, d, n_kv_heads=nkv)[0] * dy))
+    rng = np.random.default_rng(3)
+    eps = 1e-4
+    for name in ("wk", "wv", "wq", None):
+        arr = x if name is None else w[name]
+        grad = dx if name is None else g[name]
+        for _ in range(6):
+            idx = tuple(rng.integers(0, n) for n in arr.shape)
+            def at(delta):
+                a2 = arr.copy(); a2[idx] += delta
+                return loss(a2, w) if name is None else loss(x, dict(w, **{name: a2}))
+            fd = (-at(2 * eps) + 8 * at(eps) - 8 * at(-eps) + at(-2 * eps)) / (12 * eps)
+            assert abs(fd - grad[idx]) <= 1e-7 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])
