@@ -172,7 +172,7 @@ def main():
             cores = os.cpu_count() or 1
         x0, dy0 = acts[0]
         t0 = time.perf_counter()
-        yo, cache = O.layer_forward(x0, w_np[0], s.n_heads, s.head_dim, s.rms_eps, s.rope_base)
+        yo, cache = O.layer_forward(x0, w_np[0], s.n_heads, s.head_dim, s.rms_eps, s.rope_base, s.kv_heads)
         dxo, go = O.layer_backward(dy0, w_np[0], cache)
         ct = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round((f + b) / ct / 1e12, 4), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",

@@ -10,10 +10,11 @@
  * Section 3.2 samples from each accelerator type.
  *
  * Layer (pre-norm Llama decoder layer, no bias, no dropout), T = micro_batch*seq
- * tokens, H hidden, A = n_heads*head_dim, F = ffn:
+ * tokens, H hidden, A = n_heads*head_dim, Akv = n_kv_heads*head_dim, F = ffn:
  *     xn = rmsnorm(x; g_attn)          q,k,v = xn Wq^T, xn Wk^T, xn Wv^T
  *     q,k <- rope(q), rope(k)          (pairs (i, i+head_dim/2), angle pos*base^(-2i/d))
- *     a  = causal_softmax(q k^T / sqrt(d)) v      per (sample, head)
+ *     a  = causal_softmax(q k^T / sqrt(d)) v      per (sample, query head); query head h reads key/value
+ *                                                 head h / (n_heads / n_kv_heads)  (grouped-query attention)
  *     h  = x + a Wo^T                  hn = rmsnorm(h; g_mlp)
  *     y  = h + (silu(hn Wg^T) * (hn Wu^T)) Wd^T
  * rmsnorm(t; g) = t * g / sqrt(mean(t^2) + rms_eps).  When the shapes are one
@@ -36,7 +37,7 @@
  *    bfloat16, accumulation fp32, parameter gradients fp32.  dtype HH_F32:
  *    everything fp32.
  *  - Every pointer must be 16-byte aligned (HH_ERR_MISALIGNED otherwise).
- *  - Shapes: head_dim 64 or 128; n_kv_heads == n_heads; hidden, n_heads*head_dim
+ *  - Shapes: head_dim 64 or 128; n_kv_heads divides n_heads; hidden, n_heads*head_dim
  *    and ffn multiples of 64 for HH_BF16 and multiples of 8 for HH_F32; any
  *    seq >= 1, micro_batch >= 1; each tensor below 2^31 elements
  *    (HH_ERR_UNSUPPORTED_SHAPE otherwise).
@@ -67,7 +68,7 @@ typedef enum { HH_F32 = 0, HH_BF16 = 1 } hh_dtype;
 typedef struct {
     int32_t hidden;       /* H */
     int32_t n_heads;      /* heads held by this GPU */
-    int32_t n_kv_heads;   /* must equal n_heads */
+    int32_t n_kv_heads;   /* divides n_heads; query head h uses key/value head h / (n_heads / n_kv_heads) */
     int32_t head_dim;     /* d: 64 or 128 */
     int32_t ffn;          /* F: SwiGLU width held by this GPU */
     int32_t seq;          /* S */
@@ -77,14 +78,14 @@ typedef struct {
     int32_t dtype;        /* hh_dtype */
 } hh_layer_cfg;
 
-/* Parameters of one layer, in the storage dtype.  wq, wk, wv may be three rows
- * blocks of one [3A, H] allocation, w_gate and w_up of one [2F, H] allocation:
- * the library then runs one GEMM instead of three / two. */
+/* Parameters of one layer, in the storage dtype.  wq, wk, wv may be three row
+ * blocks of one [A + 2*Akv, H] allocation, w_gate and w_up of one [2F, H]
+ * allocation: the library then runs one GEMM instead of three / two. */
 typedef struct {
     const void *g_attn;  /* [H]    */
     const void *wq;      /* [A, H] */
-    const void *wk;      /* [A, H] */
-    const void *wv;      /* [A, H] */
+    const void *wk;      /* [Akv, H] */
+    const void *wv;      /* [Akv, H] */
     const void *wo;      /* [H, A] */
     const void *g_mlp;   /* [H]    */
     const void *w_gate;  /* [F, H] */

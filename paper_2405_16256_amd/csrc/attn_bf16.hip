@@ -153,7 +153,7 @@ __device__ __forceinline__ void load_qfrag(bf16x8 (&f)[D / 16], __amdgpu_buffer_
 //   (accumulator, running maximum, sum) are merged through LDS at the end, always in the same order.
 template <int D, int NPAR>
 __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
-                                                       bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh, int B) {
+                                                       bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh, int nkv, int B) {
     using TL = Tile<D>;
     constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
     extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
@@ -162,6 +162,7 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
     const int nhb = nh * B;
     const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
+    const int kcol = A + (h / (nh / nkv)) * D;   // this query head's key head; its value head is nkv*D further
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int wq = wave & 3, par = wave >> 2;
     const int q0 = qb * 128 + wq * 32;
@@ -176,8 +177,8 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
 #pragma unroll
         for (int p = 0; p < NPAR; p++) {
             const uint32_t kv = (uint32_t)(NPAR * s + p) * 64u;
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, A + h * D);
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, kcol);
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, kcol + nkv * D);
         }
     };
     issue(0, 0);
@@ -332,13 +333,14 @@ template <int D, int NPAR>
 __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                           const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                           const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                          bf16_t* __restrict__ dqkv, int S, int nh, int B) {
+                                                          bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
     using TL = Tile<D>;
     constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
     extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
     const int nhb = nh * B;   // flattened grid, last query block first (see k_attn_fwd)
     const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
+    const int kcol = A + (h / (nh / nkv)) * D;   // this query head's key head; its value head is nkv*D further
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int wq = wave & 3, par = wave >> 2;
     const int q0 = qb * 128 + wq * 32;
@@ -353,8 +355,8 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd
 #pragma unroll
         for (int p = 0; p < NPAR; p++) {
             const uint32_t kv = (uint32_t)(NPAR * s + p) * 64u;
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, A + h * D);
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, 2 * A + h * D);
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, kcol);
+            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, kcol + nkv * D);
         }
     };
     issue(0, 0);
@@ -457,7 +459,7 @@ template <int D>
 __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                             const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                             const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                            bf16_t* __restrict__ dqkv, int S, int nh, int B) {
+                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
     using TL = Tile<D>;
     constexpr int NW = KVTHREADS / WAVE;
     constexpr int STAGE = 2 * TL::BYTES;                              // Q tile | dO tile
@@ -465,11 +467,11 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const char* sKV = smem + 2 * STAGE;
     float* sLD = reinterpret_cast<float*>(smem + 2 * STAGE + 4 * TL::BYTES);
-    // flattened grid: key block first (block 0 has the most query tiles), so the long jobs of every
-    // head and sample are dispatched before the short ones
-    const int nhb = nh * B;
-    const int kb = blockIdx.x / nhb, h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
-    const int A = nh * D;
+    // flattened grid over (key block, key/value head, sample): key block first (block 0 has the most query
+    // tiles), so the long jobs of every head and sample are dispatched before the short ones
+    const int nkb = nkv * B;
+    const int kb = blockIdx.x / nkb, hk = (blockIdx.x % nkb) % nkv, b = (blockIdx.x % nkb) / nkv;
+    const int A = nh * D, G = nh / nkv;      // the key/value head collects the gradients of query heads hk*G .. +G-1
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int kw = wave & 3, qh = wave >> 2;
     const int k0 = kb * 128 + kw * 32;
@@ -480,25 +482,30 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     const i32x4 rswdo = make_rsrc_words(dout, do_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const typename TL::Offsets offs = TL::offsets();
-    auto issue = [&](int st, int q) {
+    // work items: for each of the G query heads, the query tiles from the key block's diagonal to the end
+    const int nsteps = (S - kb * 128 + 63) / 64, nitems = G * nsteps;
+    auto head_of = [&](int it) { return hk * G + it / nsteps; };
+    auto tile_of = [&](int it) { return kb * 128 + (it % nsteps) * 64; };
+    auto issue = [&](int st, int it) {
+        const int h = head_of(it), q = tile_of(it);
         TL::template dma<NW>(lds0 + st * STAGE, rsw, tokb + q, ld, h * D);
         TL::template dma<NW>(lds0 + st * STAGE + TL::BYTES, rswdo, tokb + q, A, h * D);
     };
-    // lse (log2 domain) and delta of the 64 queries starting at q: thread i < 64 -> lse, 64 <= i < 128 -> delta
-    auto stat = [&](int q) -> float {
-        const int i = threadIdx.x & 63, qq = q + i;
+    // lse (log2 domain) and delta of the 64 queries of item it: thread i < 64 -> lse, 64 <= i < 128 -> delta
+    auto stat = [&](int it) -> float {
+        const int i = threadIdx.x & 63, qq = tile_of(it) + i;
         if (threadIdx.x >= 128 || qq >= S) return 0.f;
-        const size_t at = ((size_t)b * nh + h) * S + qq;
+        const size_t at = ((size_t)b * nh + head_of(it)) * S + qq;
         return threadIdx.x < 64 ? lse[at] * LOG2E : dvec[at];
     };
     // K, V of keys kb*128 .. +127: resident for the whole kernel (first wait_dma below covers them)
 #pragma unroll
     for (int i = 0; i < 2; i++) {
-        TL::template dma<NW>(lds0 + 2 * STAGE + i * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + h * D);
-        TL::template dma<NW>(lds0 + 2 * STAGE + (2 + i) * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, 2 * A + h * D);
+        TL::template dma<NW>(lds0 + 2 * STAGE + i * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + hk * D);
+        TL::template dma<NW>(lds0 + 2 * STAGE + (2 + i) * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + (nkv + hk) * D);
     }
-    issue(0, kb * 128);
-    float nstat = stat(kb * 128);
+    issue(0, 0);
+    float nstat = stat(0);
     const char* sKw = sKV + (kw >> 1) * TL::BYTES;        // tile holding this wave's 32 keys (row block kw & 1)
     const char* sVw = sKw + 2 * TL::BYTES;
     const float sc = 1.0f / sqrtf((float)D);
@@ -509,12 +516,12 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
 #pragma unroll
         for (int r = 0; r < 16; r++) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-    int t = 0;
-    for (int qt = kb * 128; qt < S; qt += 64, t++) {
-        if (threadIdx.x < 128) sLD[(t & 1) * 128 + threadIdx.x] = nstat;   // lse / delta of tile t (fetched a step ago)
+    for (int t = 0; t < nitems; t++) {
+        const int qt = tile_of(t);
+        if (threadIdx.x < 128) sLD[(t & 1) * 128 + threadIdx.x] = nstat;   // lse / delta of item t (fetched a step ago)
         wait_dma();
-        __syncthreads();   // tile t and its lse/delta are in LDS for everyone; everyone has finished with tile t-1
-        if (qt + 64 < S) { issue((t + 1) & 1, qt + 64); nstat = stat(qt + 64); }
+        __syncthreads();   // item t and its lse/delta are in LDS for everyone; everyone has finished with item t-1
+        if (t + 1 < nitems) { issue((t + 1) & 1, t + 1); nstat = stat(t + 1); }
         const char* sQ = smem + (t & 1) * STAGE;
         const char* sO = sQ + TL::BYTES;
         const float* sL = sLD + (t & 1) * 128;
@@ -598,8 +605,8 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     }
     __syncthreads();
     if (qh == 0 && key < S) {
-        bf16_t* krow = dqkv + (size_t)(tokb + key) * ld + A + h * D;
-        bf16_t* vrow = krow + A;
+        bf16_t* krow = dqkv + (size_t)(tokb + key) * ld + A + hk * D;
+        bf16_t* vrow = krow + nkv * D;
 #pragma unroll
         for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
@@ -629,29 +636,30 @@ static hipError_t set_lds(K kern, int bytes) {
 static bool split_keys(unsigned grid, int S) { return S >= 1024 && grid <= 2 * 256; }
 
 template <int D>
-static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float* lse, int B, int S, int nh, hipStream_t st) {
+static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float* lse, int B, int S, int nh, int nkv, hipStream_t st) {
     const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
     if (split_keys(grid, S)) {
         constexpr int LDS = 8 * Tile<D>::BYTES;
         hipError_t e = set_lds(k_attn_fwd<D, 2>, LDS);
         if (e != hipSuccess) return e;
-        k_attn_fwd<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, B);
+        k_attn_fwd<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, nkv, B);
     } else {
         constexpr int LDS = 4 * Tile<D>::BYTES;
         hipError_t e = set_lds(k_attn_fwd<D, 1>, LDS);
         if (e != hipSuccess) return e;
-        k_attn_fwd<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, B);
+        k_attn_fwd<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (bf16_t*)o, lse, S, nh, nkv, B);
     }
     return hipGetLastError();
 }
 
 template <int D>
 static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, const void* dout, uint32_t do_bytes,
-                        const float* lse, float* dvec, void* dqkv, int B, int S, int nh, hipStream_t st) {
+                        const float* lse, float* dvec, void* dqkv, int B, int S, int nh, int nkv, hipStream_t st) {
     constexpr int LDS_KV = 8 * Tile<D>::BYTES + 1024;
     hipError_t e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
+    const unsigned grid_kv = (unsigned)((S + 127) / 128) * nkv * B;
     const long rows = (long)B * S * nh;
     k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
     if (split_keys(grid, S)) {
@@ -659,34 +667,34 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
         e = set_lds(k_attn_bwd_dq<D, 2>, LDS);
         if (e != hipSuccess) return e;
         k_attn_bwd_dq<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                             (bf16_t*)dqkv, S, nh, B);
+                                                             (bf16_t*)dqkv, S, nh, nkv, B);
     } else {
         constexpr int LDS = 4 * Tile<D>::BYTES;
         e = set_lds(k_attn_bwd_dq<D, 1>, LDS);
         if (e != hipSuccess) return e;
         k_attn_bwd_dq<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                         (bf16_t*)dqkv, S, nh, B);
+                                                         (bf16_t*)dqkv, S, nh, nkv, B);
     }
-    k_attn_bwd_dkv<D><<<grid, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
-                                                       dvec, (bf16_t*)dqkv, S, nh, B);
+    k_attn_bwd_dkv<D><<<grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
+                                                          dvec, (bf16_t*)dqkv, S, nh, nkv, B);
     return hipGetLastError();
 }
 
-hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st) {
+hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st) {
     const long bytes = (long)B * S * ld * 2;
     if (bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
-    if (d == 128) return fwd_d<128>(qkv, ld, (uint32_t)bytes, o, lse, B, S, nh, st);
-    if (d == 64) return fwd_d<64>(qkv, ld, (uint32_t)bytes, o, lse, B, S, nh, st);
+    if (d == 128) return fwd_d<128>(qkv, ld, (uint32_t)bytes, o, lse, B, S, nh, nkv, st);
+    if (d == 64) return fwd_d<64>(qkv, ld, (uint32_t)bytes, o, lse, B, S, nh, nkv, st);
     return hipErrorInvalidValue;
 }
 
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                         void* dqkv, int B, int S, int nh, int d, hipStream_t st) {
+                         void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st) {
     const long bytes = (long)B * S * ld * 2;
     const long do_bytes = (long)B * S * nh * d * 2;
     if (bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
-    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, st);
-    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, st);
+    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, nkv, st);
+    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, nkv, st);
     return hipErrorInvalidValue;
 }
 

@@ -191,23 +191,23 @@ __global__ __launch_bounds__(TPB) void k_colsum_reduce(const float* __restrict__
 }
 
 // --------------------------------------------------------------------- RoPE
-// One thread rotates V pairs (i, i + d/2) of one head of one token, for q or k.
+// One thread rotates V pairs (i, i + d/2) of one of the nrot heads that start at column 0 of a token's row
+// (the query heads followed by the key heads).
 template <typename T>
-__global__ __launch_bounds__(TPB) void k_rope(T* __restrict__ qkv, int ld, int Ttok, int S, int nh, int d,
+__global__ __launch_bounds__(TPB) void k_rope(T* __restrict__ qkv, int ld, int Ttok, int S, int nrot, int d,
                                               const float* __restrict__ table, int table_seq, float sin_sign) {
     constexpr int V = Vec<T>::N;
     const int half = d / 2;
     const int vph = half / V;               // vectors per head-half
-    const long total = (long)Ttok * 2 * nh * vph;
+    const long total = (long)Ttok * nrot * vph;
     const long idx = (long)blockIdx.x * TPB + threadIdx.x;
     if (idx >= total) return;
     const int iv = (int)(idx % vph);
     long rest = idx / vph;
-    const int head = (int)(rest % nh); rest /= nh;
-    const int which = (int)(rest % 2);
-    const int t = (int)(rest / 2);
+    const int head = (int)(rest % nrot);
+    const int t = (int)(rest / nrot);
     const int pos = t % S;
-    T* p = qkv + (size_t)t * ld + (size_t)which * nh * d + head * d + iv * V;
+    T* p = qkv + (size_t)t * ld + (size_t)head * d + iv * V;
     const float* cs = table + ((size_t)pos * half + iv * V);
     const float* sn = cs + (size_t)table_seq * half;
     float a[V], b[V], oa[V], ob[V];
@@ -315,15 +315,15 @@ hipError_t colsum_reduce(const float* partial, int nblk, int H, float* out, int 
     return hipGetLastError();
 }
 
-hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nh, int d, const float* table, int table_seq,
+hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nrot, int d, const float* table, int table_seq,
                 int backward, hipStream_t st) {
     const float sgn = backward ? -1.0f : 1.0f;
     if (dtype == DT_BF16) {
-        const long n = (long)T * 2 * nh * (d / 2 / Vec<bf16_t>::N);
-        k_rope<bf16_t><<<nblocks(n), TPB, 0, st>>>((bf16_t*)qkv, ld, T, S, nh, d, table, table_seq, sgn);
+        const long n = (long)T * nrot * (d / 2 / Vec<bf16_t>::N);
+        k_rope<bf16_t><<<nblocks(n), TPB, 0, st>>>((bf16_t*)qkv, ld, T, S, nrot, d, table, table_seq, sgn);
     } else {
-        const long n = (long)T * 2 * nh * (d / 2 / Vec<float>::N);
-        k_rope<float><<<nblocks(n), TPB, 0, st>>>((float*)qkv, ld, T, S, nh, d, table, table_seq, sgn);
+        const long n = (long)T * nrot * (d / 2 / Vec<float>::N);
+        k_rope<float><<<nblocks(n), TPB, 0, st>>>((float*)qkv, ld, T, S, nrot, d, table, table_seq, sgn);
     }
     return hipGetLastError();
 }

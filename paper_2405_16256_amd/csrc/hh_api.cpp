@@ -18,23 +18,23 @@
 namespace hh {
 hipError_t gemm_bf16(const GemmDesc& g, hipStream_t st);
 hipError_t gemm_f32(const GemmDesc& g, hipStream_t st);
-hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st);
+hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st);
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                         void* dqkv, int B, int S, int nh, int d, hipStream_t st);
-hipError_t attn_f32_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st);
+                         void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st);
+hipError_t attn_f32_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st);
 hipError_t attn_f32_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                        void* dqkv, int B, int S, int nh, int d, hipStream_t st);
+                        void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st);
 
 hipError_t gemm(int dtype, const GemmDesc& g, hipStream_t st) {
     return dtype == DT_BF16 ? gemm_bf16(g, st) : gemm_f32(g, st);
 }
-hipError_t attn_fwd(int dtype, const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int d, hipStream_t st) {
-    return dtype == DT_BF16 ? attn_bf16_fwd(qkv, ld, o, lse, B, S, nh, d, st) : attn_f32_fwd(qkv, ld, o, lse, B, S, nh, d, st);
+hipError_t attn_fwd(int dtype, const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_bf16_fwd(qkv, ld, o, lse, B, S, nh, nkv, d, st) : attn_f32_fwd(qkv, ld, o, lse, B, S, nh, nkv, d, st);
 }
 hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                    void* dqkv, int B, int S, int nh, int d, hipStream_t st) {
-    return dtype == DT_BF16 ? attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, d, st)
-                            : attn_f32_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, d, st);
+                    void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, nkv, d, st)
+                            : attn_f32_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, nkv, d, st);
 }
 }  // namespace hh
 
@@ -111,11 +111,11 @@ static int check_cfg(const hh_layer_cfg* c) {
     if (c->hidden <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->ffn <= 0 || c->seq <= 0 || c->micro_batch <= 0)
         return fail(HH_ERR_INVALID_ARG, "cfg has a non-positive dimension");
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(HH_ERR_INVALID_ARG, "cfg.rms_eps must be >= 0 and rope_base > 0");
-    if (c->n_kv_heads != c->n_heads)
-        return fail(HH_ERR_UNSUPPORTED_SHAPE, "n_kv_heads (%d) must equal n_heads (%d)", c->n_kv_heads, c->n_heads);
+    if (c->n_kv_heads <= 0 || c->n_heads % c->n_kv_heads)
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "n_kv_heads (%d) must be positive and divide n_heads (%d)", c->n_kv_heads, c->n_heads);
     if (c->head_dim != 64 && c->head_dim != 128) return fail(HH_ERR_UNSUPPORTED_SHAPE, "head_dim %d: only 64 and 128", c->head_dim);
     const int mult = c->dtype == HH_BF16 ? 64 : 8;
-    const long A = (long)c->n_heads * c->head_dim;
+    const long A = (long)c->n_heads * c->head_dim;   // the kv width n_kv_heads*head_dim is a multiple of 64 as well
     if (c->hidden % mult || A % mult || c->ffn % mult)
         return fail(HH_ERR_UNSUPPORTED_SHAPE, "hidden, n_heads*head_dim and ffn must be multiples of %d for this dtype", mult);
     if (c->hidden > 32768) return fail(HH_ERR_UNSUPPORTED_SHAPE, "hidden %d exceeds 32768", c->hidden);
@@ -158,13 +158,13 @@ static int check_grads(const hh_layer_grads* g) {
 static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct Dims {
-    int T, H, A, F, S, B, nh, d, dt;
+    int T, H, A, Akv, Q3, F, S, B, nh, nkv, d, dt;   // Akv = nkv*d; Q3 = A + 2*Akv: width of a q|k|v row
     size_t es;
 };
 static Dims dims_of(const hh_layer_cfg* c) {
     Dims d;
     d.S = c->seq; d.B = c->micro_batch; d.T = c->seq * c->micro_batch; d.H = c->hidden; d.nh = c->n_heads; d.d = c->head_dim;
-    d.A = c->n_heads * c->head_dim; d.F = c->ffn; d.dt = c->dtype == HH_BF16 ? DT_BF16 : DT_F32; d.es = dt_size(d.dt);
+    d.A = c->n_heads * c->head_dim; d.nkv = c->n_kv_heads; d.Akv = d.nkv * d.d; d.Q3 = d.A + 2 * d.Akv; d.F = c->ffn; d.dt = c->dtype == HH_BF16 ? DT_BF16 : DT_F32; d.es = dt_size(d.dt);
     return d;
 }
 
@@ -177,7 +177,7 @@ static SavedLayout saved_layout(const Dims& d) {
     auto take = [&](size_t bytes) { size_t o = off; off += up256(bytes); return o; };
     const size_t T = d.T;
     s.xn = take(T * d.H * d.es);
-    s.qkv = take(T * 3 * d.A * d.es);
+    s.qkv = take(T * d.Q3 * d.es);
     s.a = take(T * d.A * d.es);
     s.h = take(T * d.H * d.es);
     s.hn = take(T * d.H * d.es);
@@ -202,7 +202,7 @@ static WorkLayout work_layout(const Dims& d) {
     w.dhn = take(T * d.H * d.es);          // d(hn), later d(xn)
     w.dh = take(T * d.H * d.es);
     w.da = take(T * d.A * d.es);
-    w.dqkv = take(T * 3 * d.A * d.es);
+    w.dqkv = take(T * d.Q3 * d.es);
     w.dvec = take((size_t)d.B * d.nh * d.S * 4);
     w.partial = take((size_t)rmsnorm_bwd_blocks(d.T) * d.H * 4);
     w.gemm_ws = take(d.dt == DT_BF16 ? GEMM_WS_BYTES : 0);
@@ -235,7 +235,7 @@ extern "C" int hh_layer_flops(const hh_layer_cfg* cfg, double* fwd_flop, double*
     TRY(check_cfg(cfg));
     const Dims d = dims_of(cfg);
     const double T = d.T;
-    const double gemm = T * (8.0 * d.A * d.H + 6.0 * (double)d.H * d.F);
+    const double gemm = T * (2.0 * (d.Q3 + d.A) * d.H + 6.0 * (double)d.H * d.F);
     const double attn = 4.0 * d.d * d.B * d.nh * ((double)d.S * (d.S + 1) / 2);
     if (fwd_flop) *fwd_flop = gemm + attn;
     if (bwd_flop) *bwd_flop = 2.0 * (gemm + attn);
@@ -358,17 +358,20 @@ static int layer_fwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     ctx->gemm_ws = d.dt == DT_BF16 ? at(ws, wl.gemm_ws) : nullptr;
 
     TR(HH_TRACE_ELEMENTWISE, 2.0 * T * H * es, rmsnorm_fwd(dt, x, w->g_attn, xn, r1, T, H, cfg->rms_eps, st));
+    // q | k | v rows of width A, Akv, Akv (Akv < A with grouped-query attention)
+    const int Akv = d.Akv, Q3 = d.Q3;
+    const int part_w[3] = {A, Akv, Akv}, part_c[3] = {0, A, A + Akv};
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
-                            (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
+                            (const char*)w->wv == (const char*)w->wk + (size_t)Akv * H * es;
     if (qkv_packed) {
-        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, 3 * A, H, xn, H, w->wq, H, qkv, 3 * A), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, Q3, H, xn, H, w->wq, H, qkv, Q3), st));
     } else {
         const void* ws3[3] = {w->wq, w->wk, w->wv};
         for (int i = 0; i < 3; i++)
-            HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, A, H, xn, H, ws3[i], H, at(qkv, (size_t)i * A * es), 3 * A), st));
+            HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, part_w[i], H, xn, H, ws3[i], H, at(qkv, (size_t)part_c[i] * es), Q3), st));
     }
-    TR(HH_TRACE_ELEMENTWISE, 4.0 * T * A * es, rope(dt, qkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 0, st));
-    TR(HH_TRACE_ATTN_FWD, attn_flop(d), attn_fwd(dt, qkv, 3 * A, a, lse, d.B, d.S, d.nh, d.d, st));
+    TR(HH_TRACE_ELEMENTWISE, 2.0 * T * (A + Akv) * es, rope(dt, qkv, Q3, T, d.S, d.nh + d.nkv, d.d, ctx->rope_table, ctx->rope_seq, 0, st));
+    TR(HH_TRACE_ATTN_FWD, attn_flop(d), attn_fwd(dt, qkv, Q3, a, lse, d.B, d.S, d.nh, d.nkv, d.d, st));
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_NT, T, H, A, a, A, w->wo, A, h, H, x, H), st));
     TR(HH_TRACE_ELEMENTWISE, 2.0 * T * H * es, rmsnorm_fwd(dt, h, w->g_mlp, hn, r2, T, H, cfg->rms_eps, st));
     const bool gu_packed = (const char*)w->w_up == (const char*)w->w_gate + (size_t)F * H * es;
@@ -446,25 +449,27 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     // attention branch: h = x + a Wo^T
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, H, A, T, dh, H, a, A, g->wo, A, nullptr, 0, 1, acc), st));
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
-    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, 3 * A, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.d, st));
-    TR(HH_TRACE_ELEMENTWISE, 4.0 * T * A * es, rope(dt, dqkv, 3 * A, T, d.S, d.nh, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
+    const int Akv = d.Akv, Q3 = d.Q3;
+    const int part_w[3] = {A, Akv, Akv}, part_c[3] = {0, A, A + Akv};
+    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, Q3, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.nkv, d.d, st));
+    TR(HH_TRACE_ELEMENTWISE, 2.0 * T * (A + Akv) * es, rope(dt, dqkv, Q3, T, d.S, d.nh + d.nkv, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
-                            (const char*)w->wv == (const char*)w->wk + (size_t)A * H * es;
-    const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)A * H * 4;
+                            (const char*)w->wv == (const char*)w->wk + (size_t)Akv * H * es;
+    const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)Akv * H * 4;
     if (dqkv_packed) {
-        HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, 3 * A, H, T, dqkv, 3 * A, xn, H, g->wq, H, nullptr, 0, 1, acc), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, Q3, H, T, dqkv, Q3, xn, H, g->wq, H, nullptr, 0, 1, acc), st));
     } else {
         float* gs[3] = {g->wq, g->wk, g->wv};
         for (int i = 0; i < 3; i++)
-            HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, A, H, T, at(dqkv, (size_t)i * A * es), 3 * A, xn, H, gs[i], H, nullptr, 0, 1, acc), st));
+            HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, part_w[i], H, T, at(dqkv, (size_t)part_c[i] * es), Q3, xn, H, gs[i], H, nullptr, 0, 1, acc), st));
     }
     void* dxn = dhn;
     if (qkv_packed) {
-        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, 3 * A, dqkv, 3 * A, w->wq, H, dxn, H), st));
+        HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, Q3, dqkv, Q3, w->wq, H, dxn, H), st));
     } else {
         const void* ws3[3] = {w->wq, w->wk, w->wv};
         for (int i = 0; i < 3; i++)
-            HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, A, at(dqkv, (size_t)i * A * es), 3 * A, ws3[i], H, dxn, H,
+            HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, H, part_w[i], at(dqkv, (size_t)part_c[i] * es), Q3, ws3[i], H, dxn, H,
                                   i ? dxn : nullptr, H), st));
     }
     TR(HH_TRACE_ELEMENTWISE, 4.0 * T * H * es, rmsnorm_bwd(dt, dxn, x, r1, w->g_attn, dh, dx, partial, T, H, st));              // dx = dh + norm-bwd
@@ -645,7 +650,7 @@ extern "C" int hh_layer_profile(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_laye
     double ff = 0, bf = 0;
     (void)hh_layer_flops(cfg, &ff, &bf);
     const size_t A = d.A;
-    const uint64_t nparam = 2ull * d.H + 4ull * A * d.H + 3ull * (uint64_t)d.F * d.H;
+    const uint64_t nparam = 2ull * d.H + (2ull * A + 2ull * d.Akv) * d.H + 3ull * (uint64_t)d.F * d.H;
     for (int l = 0; l < k; l++) {
         hh_profile_rec& r = out[l];
         r.layer = l;

@@ -40,10 +40,10 @@ hipError_t rmsnorm_bwd(int dtype, const void* dxn, const void* x, const float* r
                        const void* dres, void* dx, float* partial, int T, int H, hipStream_t st);
 hipError_t colsum_reduce(const float* partial, int nblk, int H, float* out, int accumulate, hipStream_t st);
 
-// In-place rotary embedding of the q and k column blocks of a [T, ld] buffer
-// (q at column 0, k at column nh*d).  table = cos[table_seq][d/2] followed by sin[table_seq][d/2],
-// table_seq >= S.  backward: rotate by -angle.
-hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nh, int d, const float* table, int table_seq,
+// In-place rotary embedding of the first nrot heads (query heads, then key heads) of every row of a
+// [T, ld] buffer.  table = cos[table_seq][d/2] followed by sin[table_seq][d/2], table_seq >= S.
+// backward: rotate by -angle.
+hipError_t rope(int dtype, void* qkv, int ld, int T, int S, int nrot, int d, const float* table, int table_seq,
                 int backward, hipStream_t st);
 
 // gu[T,2F] = (gate | up);  m = silu(gate)*up
@@ -51,12 +51,13 @@ hipError_t swiglu_fwd(int dtype, const void* gu, void* m, int T, int F, hipStrea
 // dgu[T,2F] = (dgate | dup), and m recomputed
 hipError_t swiglu_bwd(int dtype, const void* dm, const void* gu, void* dgu, void* m, int T, int F, hipStream_t st);
 
-// Causal attention over a [T, ld] buffer holding q | k | v column blocks of width nh*d.
-// o [T, nh*d]; lse [B, nh, S] natural-log sum-exp of the scaled scores.
+// Causal attention over a [T, ld] buffer holding q | k | v column blocks of width nh*d, nkv*d, nkv*d;
+// query head h uses key/value head h / (nh / nkv).  o [T, nh*d]; lse [B, nh, S] natural-log sum-exp of
+// the scaled scores.
 hipError_t attn_fwd(int dtype, const void* qkv, int ld, void* o, float* lse,
-                    int B, int S, int nh, int d, hipStream_t st);
-// dqkv [T, ld] receives dq | dk | dv.  dvec: scratch [B, nh, S] floats.
+                    int B, int S, int nh, int nkv, int d, hipStream_t st);
+// dqkv [T, ld] receives dq | dk | dv in the same layout.  dvec: scratch [B, nh, S] floats.
 hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const void* dout, const float* lse,
-                    float* dvec, void* dqkv, int B, int S, int nh, int d, hipStream_t st);
+                    float* dvec, void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st);
 
 }  // namespace hh

@@ -35,16 +35,16 @@ class DeviceLayer:
     def __init__(self, w: dict, s: I.LayerShape, bf16: bool, packed: bool = True):
         self.s, self.bf16 = s, bf16
         dt = torch.bfloat16 if bf16 else torch.float32
-        H, A, F = s.hidden, s.attn, s.ffn
+        H, A, Akv, F = s.hidden, s.attn, s.attn_kv, s.ffn
         self.w, self.g = {}, {}
         if packed:
-            wqkv = torch.empty(3 * A, H, dtype=dt, device=DEV)
+            wqkv = torch.empty(A + 2 * Akv, H, dtype=dt, device=DEV)
             wgu = torch.empty(2 * F, H, dtype=dt, device=DEV)
-            gqkv = torch.zeros(3 * A, H, dtype=torch.float32, device=DEV)
+            gqkv = torch.zeros(A + 2 * Akv, H, dtype=torch.float32, device=DEV)
             ggu = torch.zeros(2 * F, H, dtype=torch.float32, device=DEV)
-            for i, n in enumerate(("wq", "wk", "wv")):
-                self.w[n] = wqkv[i * A:(i + 1) * A]
-                self.g[n] = gqkv[i * A:(i + 1) * A]
+            for n, (lo, hi) in (("wq", (0, A)), ("wk", (A, A + Akv)), ("wv", (A + Akv, A + 2 * Akv))):
+                self.w[n] = wqkv[lo:hi]
+                self.g[n] = gqkv[lo:hi]
             for i, n in enumerate(("w_gate", "w_up")):
                 self.w[n] = wgu[i * F:(i + 1) * F]
                 self.g[n] = ggu[i * F:(i + 1) * F]
@@ -65,7 +65,7 @@ class DeviceLayer:
 
 def cfg_of(s: I.LayerShape, bf16: bool) -> hh.hh_layer_cfg:
     return hh.make_cfg(s.hidden, s.n_heads, s.head_dim, s.ffn, s.seq, s.micro_batch, s.rms_eps, s.rope_base,
-                       hh.HH_BF16 if bf16 else hh.HH_F32)
+                       hh.HH_BF16 if bf16 else hh.HH_F32, n_kv_heads=s.kv_heads)
 
 
 def stream_ptr() -> int:

@@ -41,6 +41,13 @@ def test_flops_match_the_model_flop_convention():
     assert abs((f2 + b2) - 2.590e12) / 2.590e12 < 1e-3
     f1, b1 = hh.hh_layer_flops(hh.make_cfg(256, 4, 64, 688, 128, 1, dtype=hh.HH_F32))
     assert abs((f1 + b1) - 6.325e8) / 6.325e8 < 1e-3
+    # grouped-query attention: the key and value projections shrink to n_kv_heads*head_dim columns
+    T, H, A, Akv, F, S, nh, d = 2048, 8192, 8192, 1024, 28672, 2048, 64, 128
+    fg, bg = hh.hh_layer_flops(hh.make_cfg(H, nh, d, F, S, 1, n_kv_heads=8))
+    assert fg == T * (2 * H * (A + 2 * Akv) + 2 * A * H + 6 * H * F) + 4 * d * nh * S * (S + 1) // 2 and bg == 2 * fg
+    sg, _ = hh.hh_layer_sizes(hh.make_cfg(H, nh, d, F, S, 1, n_kv_heads=8))
+    sm, _ = hh.hh_layer_sizes(hh.make_cfg(H, nh, d, F, S, 1))
+    assert sm - sg == 2 * T * 2 * (A - Akv)          # the saved q|k|v rows are narrower
 
 
 def test_sizes():
@@ -62,7 +69,8 @@ def test_sizes():
     (dict(head_dim=96), hh.HH_ERR_UNSUPPORTED_SHAPE),
     (dict(hidden=4100), hh.HH_ERR_UNSUPPORTED_SHAPE),
     (dict(ffn=11000), hh.HH_ERR_UNSUPPORTED_SHAPE),
-    (dict(n_kv_heads=8), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    (dict(n_kv_heads=5), hh.HH_ERR_UNSUPPORTED_SHAPE),      # does not divide 32 heads
+    (dict(n_kv_heads=0), hh.HH_ERR_UNSUPPORTED_SHAPE),
     (dict(seq=0), hh.HH_ERR_INVALID_ARG),
     (dict(micro_batch=-1), hh.HH_ERR_INVALID_ARG),
     (dict(dtype=7), hh.HH_ERR_INVALID_ARG),

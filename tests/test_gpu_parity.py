@@ -46,7 +46,7 @@ def check_layer(ctx, s, bf16, seed, packed=True, label=""):
     g = layer.grads_np()
     say("  gpu done %.2fs; oracle..." % (time.time() - t0))
     t0 = time.time()
-    yo, cache = O.layer_forward(x, w, s.n_heads, s.head_dim, s.rms_eps, s.rope_base)
+    yo, cache = O.layer_forward(x, w, s.n_heads, s.head_dim, s.rms_eps, s.rope_base, s.kv_heads)
     dxo, go = O.layer_backward(dy, w, cache)
     say("  oracle done %.1fs" % (time.time() - t0))
     tol_out = TOL_BF16_OUT if bf16 else TOL_F32
@@ -192,7 +192,7 @@ def test_stage_step_matches_oracle(ctx, bf16, shape, k, M):
     s = shape
     say("[case] stage bf16=%s shape=%s k=%d M=%d" % (bf16, s, k, M))
     ws_np, acts, layers, ys, dxs = run_stage(ctx, s, bf16, 41, k, M)
-    yo, dxo, go = O.stage_step([a[0] for a in acts], [a[1] for a in acts], ws_np, s.n_heads, s.head_dim, s.rms_eps, s.rope_base)
+    yo, dxo, go = O.stage_step([a[0] for a in acts], [a[1] for a in acts], ws_np, s.n_heads, s.head_dim, s.rms_eps, s.rope_base, s.kv_heads)
     tol_out = TOL_BF16_OUT if bf16 else TOL_F32
     tol_grad = TOL_BF16_GRAD if bf16 else TOL_F32
     worst = 0.0
@@ -221,7 +221,7 @@ def test_stage_step_full_shape_two_layers_two_micro_batches_vs_oracle(ctx):
     ws_np, acts, layers, ys, dxs = run_stage(ctx, s, True, I.SEEDS["cfg4"], k, M)
     say("  gpu done; oracle (2 layers x 2 micro-batches)...")
     t0 = time.time()
-    yo, dxo, go = O.stage_step([a[0] for a in acts], [a[1] for a in acts], ws_np, s.n_heads, s.head_dim, s.rms_eps, s.rope_base)
+    yo, dxo, go = O.stage_step([a[0] for a in acts], [a[1] for a in acts], ws_np, s.n_heads, s.head_dim, s.rms_eps, s.rope_base, s.kv_heads)
     say("  oracle done %.1fs" % (time.time() - t0))
     worst = {}
     for m in range(M):
@@ -486,3 +486,23 @@ def test_profile_records_feed_the_pipeline_predictor(ctx):
     assert peak[0] == layers[0] * (rec.weight_bytes + 4 * rec.grad_bytes) + 4 * layers[0] * rec.saved_act_bytes
     assert 0.0 < res.mfu < 1.0 and res.tokens_per_s_per_device > 0
     say("  planned layers %s, iteration %.2f ms, MFU %.3f of a mean peak of %.0f TFLOP/s" % (layers, res.iter_ms, res.mfu, res.mean_peak_tflops))
+
+
+# ------------------------------------------------- grouped-query attention
+def test_f32_grouped_query_attention(ctx):
+    check_layer(ctx, I.LayerShape(128, 4, 64, 96, 70, 2, n_kv_heads=2), False, 71, label="f32-gqa")
+    check_layer(ctx, I.LayerShape(128, 4, 64, 96, 33, 1, n_kv_heads=1), False, 72, packed=False, label="f32-mqa-unpacked")
+
+
+def test_bf16_grouped_query_attention_small_and_long(ctx):
+    check_layer(ctx, I.LayerShape(512, 8, 64, 512, 200, 2, n_kv_heads=2), True, 73, label="bf16-gqa-d64")
+    check_layer(ctx, I.LayerShape(512, 4, 128, 512, 130, 1, n_kv_heads=1), True, 74, packed=False, label="bf16-mqa-unpacked")
+    # long ragged sequence: key tiles split between two wave groups, four query heads per key/value head
+    check_layer(ctx, I.LayerShape(1024, 8, 128, 1024, 1500, 1, n_kv_heads=2), True, 75, label="bf16-gqa-long")
+
+
+def test_bf16_70b_class_tp_share_with_grouped_queries_full_size(ctx):
+    # Table 1's 70B / 140B hidden size with the public 64 query / 8 key-value heads at a TP=8 share: 8 local query heads
+    # on one local key/value head
+    s = I.LayerShape(8192, 8, 128, 3584, 4096, 1, n_kv_heads=1)
+    check_layer(ctx, s, True, 76, label="h8192-gqa-tp8")
