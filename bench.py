@@ -7,7 +7,7 @@ workload, one 140B-class TP=8-share decoder layer, one micro-batch of 4096
 tokens: forward, then backward with fp32 gradient accumulation), every kernel
 hand-written HIP behind the C-ABI.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg4-1f1b|13b|h8192-tp8] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4|cfg4-1f1b|13b|h8192-tp8|h8192-gqa-tp8|h8192-gqa] [--no-cpu-baseline]
 """
 import argparse
 import json
@@ -39,6 +39,12 @@ def workloads():
         "h8192-tp8": dict(shape=I.SHAPE_70B_TP8, k=1, M=1, seed=62,
                           name="hidden-8192 (70B/140B-class of Table 1) decoder layer at a TP=8 share, 8x128 local heads, local ffn 3584, "
                                "seq 4096, micro-batch 1, bf16 fwd+bwd"),
+        "h8192-gqa-tp8": dict(shape=I.SHAPE_70B_GQA_TP8, k=1, M=1, seed=63,
+                              name="hidden-8192 decoder layer with grouped-query attention at a TP=8 share, 8 local query heads on 1 local "
+                                   "key/value head (d 128), local ffn 3584, seq 4096, micro-batch 1, bf16 fwd+bwd"),
+        "h8192-gqa": dict(shape=I.SHAPE_70B_GQA, k=1, M=1, seed=64,
+                          name="whole hidden-8192 decoder layer (no tensor parallelism), 64 query / 8 key-value heads of 128, ffn 28672, "
+                               "seq 4096, micro-batch 1, bf16 fwd+bwd"),
         "cfg4": dict(shape=I.CFG3, k=4, M=8, seed=I.SEEDS["cfg4"],
                      name="cfg4: pipeline-stage step, 4 layers of the cfg3 shape x 8 micro-batches of seq 4096, fp32 grad accumulation"),
         "cfg4-1f1b": dict(shape=I.CFG3, k=4, M=8, live=2, seed=I.SEEDS["cfg4"],
@@ -51,7 +57,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4-1f1b", "13b", "h8192-tp8"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4-1f1b", "13b", "h8192-tp8", "h8192-gqa-tp8", "h8192-gqa"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-trace", action="store_true", help="do not time kernel families with events (no roofline object)")
     ap.add_argument("--copy-calibration", action="store_true",

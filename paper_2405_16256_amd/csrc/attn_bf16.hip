@@ -459,7 +459,8 @@ template <int D>
 __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                             const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                             const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
+                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
+                                                            int hs, float* __restrict__ part) {
     using TL = Tile<D>;
     constexpr int NW = KVTHREADS / WAVE;
     constexpr int STAGE = 2 * TL::BYTES;                              // Q tile | dO tile
@@ -467,11 +468,14 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const char* sKV = smem + 2 * STAGE;
     float* sLD = reinterpret_cast<float*>(smem + 2 * STAGE + 4 * TL::BYTES);
-    // flattened grid over (key block, key/value head, sample): key block first (block 0 has the most query
-    // tiles), so the long jobs of every head and sample are dispatched before the short ones
-    const int nkb = nkv * B;
-    const int kb = blockIdx.x / nkb, hk = (blockIdx.x % nkb) % nkv, b = (blockIdx.x % nkb) / nkv;
-    const int A = nh * D, G = nh / nkv;      // the key/value head collects the gradients of query heads hk*G .. +G-1
+    // flattened grid over (key block, sample, key/value head, slice of its query heads): key block first (block 0
+    // has the most query tiles), so the long jobs of every head and sample are dispatched before the short ones
+    const int nkb = nkv * hs * B;
+    const int kb = blockIdx.x / nkb, rem = blockIdx.x % nkb;
+    const int b = rem / (nkv * hs), hk = (rem % (nkv * hs)) / hs, ps = rem % hs;
+    // the key/value head collects the gradients of query heads hk*(nh/nkv) .. ; this workgroup sums G of them
+    // (slice ps of hs) and, when hs > 1, leaves fp32 partial sums in part[ps][dK|dV][token][nkv*D]
+    const int A = nh * D, G = nh / nkv / hs, h_first = hk * (nh / nkv) + ps * G;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int kw = wave & 3, qh = wave >> 2;
     const int k0 = kb * 128 + kw * 32;
@@ -484,7 +488,7 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     const typename TL::Offsets offs = TL::offsets();
     // work items: for each of the G query heads, the query tiles from the key block's diagonal to the end
     const int nsteps = (S - kb * 128 + 63) / 64, nitems = G * nsteps;
-    auto head_of = [&](int it) { return hk * G + it / nsteps; };
+    auto head_of = [&](int it) { return h_first + it / nsteps; };
     auto tile_of = [&](int it) { return kb * 128 + (it % nsteps) * 64; };
     auto issue = [&](int st, int it) {
         const int h = head_of(it), q = tile_of(it);
@@ -604,6 +608,41 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
             for (int r = 0; r < 16; r++) red[(kw * R + i * 16 + r) * 64 + lane] = dv[i][r];
     }
     __syncthreads();
+    if (hs > 1) {
+        // Partial sums leave through a wave-private LDS patch in the K/V area (no longer read by anyone): a lane
+        // holds 4-channel pieces of one key row, the patch hands back whole rows, 16 bytes a lane.
+        if (qh != 0) return;
+        constexpr int CH = D / 4, RP = WAVE / CH;             // 16-byte chunks per row, rows per store instruction
+        char* const patch = smem + 2 * STAGE + kw * (32 * D * 4);
+        const int Akv = nkv * D;
+        const size_t plane = (size_t)B * S * Akv;
+#pragma unroll
+        for (int which = 0; which < 2; which++) {
+            const int r_w = lane & 31;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; dt++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    float4 v;
+                    if (which == 0) {
+                        v = make_float4(dk[dt][4 * g] * sc, dk[dt][4 * g + 1] * sc, dk[dt][4 * g + 2] * sc, dk[dt][4 * g + 3] * sc);
+                    } else {
+                        const float* rp = &red[(kw * R + dt * 16 + 4 * g) * 64 + lane];
+                        v = make_float4(dv[dt][4 * g] + rp[0], dv[dt][4 * g + 1] + rp[64], dv[dt][4 * g + 2] + rp[128], dv[dt][4 * g + 3] + rp[192]);
+                    }
+                    const int chunk = 8 * dt + 2 * g + hf;
+                    *reinterpret_cast<float4*>(patch + r_w * (D * 4) + ((chunk ^ (r_w & (CH - 1))) << 4)) = v;
+                }
+            float* const dst = part + (size_t)(ps * 2 + which) * plane + (size_t)hk * D;
+#pragma unroll
+            for (int rr = 0; rr < 32; rr += RP) {
+                const int row = rr + lane / CH, chunk = lane % CH;
+                const float4 v = *reinterpret_cast<const float4*>(patch + row * (D * 4) + ((chunk ^ (row & (CH - 1))) << 4));
+                if (k0 + row < S) *reinterpret_cast<float4*>(dst + (size_t)(tokb + k0 + row) * Akv + 4 * chunk) = v;
+            }
+        }
+        return;
+    }
     if (qh == 0 && key < S) {
         bf16_t* krow = dqkv + (size_t)(tokb + key) * ld + A + hk * D;
         bf16_t* vrow = krow + nkv * D;
@@ -625,7 +664,47 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     }
 }
 
+// Sums the hs partial dK and dV planes of grouped heads in a fixed order and writes them, rounded to bf16,
+// into the k and v columns of dqkv.  A thread owns 4 consecutive channels of one token.
+__global__ __launch_bounds__(256) void k_attn_dkv_reduce(const float* __restrict__ part, int hs, long tokens, int Akv,
+                                                         bf16_t* __restrict__ dqkv, int ld, int A) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int c4 = Akv / 4;
+    if (i >= tokens * c4) return;
+    const long tok = i / c4;
+    const int c = (int)(i % c4) * 4;
+    const size_t plane = (size_t)tokens * Akv;
+    const float* p = part + (size_t)tok * Akv + c;
+    float4 k = *reinterpret_cast<const float4*>(p), v = *reinterpret_cast<const float4*>(p + plane);
+    for (int s = 1; s < hs; s++) {
+        const float4 a = *reinterpret_cast<const float4*>(p + (size_t)(2 * s) * plane);
+        const float4 b = *reinterpret_cast<const float4*>(p + (size_t)(2 * s + 1) * plane);
+        k.x += a.x; k.y += a.y; k.z += a.z; k.w += a.w;
+        v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+    }
+    bf16_t* row = dqkv + (size_t)tok * ld + A + c;
+    *reinterpret_cast<uint2*>(row) = make_uint2(pack_bf2(k.x, k.y), pack_bf2(k.z, k.w));
+    *reinterpret_cast<uint2*>(row + Akv) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
+}
+
 // ---------------------------------------------------------------- launchers
+// Into how many slices the query heads of a key/value head are cut for dK, dV: one (the workgroup of a key block sums
+// all of them in registers) unless that leaves too few workgroups to balance the causal triangle over the chip.
+static int dkv_head_slices(int B, int S, int nh, int nkv) {
+    const int G = nh / nkv;
+    const long wgs = (long)((S + 127) / 128) * nkv * B;
+    int hs = 1;
+    while (hs < G && wgs * hs < 4 * 256) {
+        do ++hs; while (G % hs);
+    }
+    return hs;
+}
+
+size_t attn_bf16_bwd_scratch_bytes(int B, int S, int nh, int nkv, int d) {
+    const int hs = dkv_head_slices(B, S, nh, nkv);
+    return hs > 1 ? (size_t)hs * 2 * B * S * nkv * d * sizeof(float) : 0;
+}
+
 template <typename K>
 static hipError_t set_lds(K kern, int bytes) {
     return bytes > 48 * 1024 ? hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) : hipSuccess;
@@ -654,12 +733,14 @@ static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float*
 
 template <int D>
 static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, const void* dout, uint32_t do_bytes,
-                        const float* lse, float* dvec, void* dqkv, int B, int S, int nh, int nkv, hipStream_t st) {
+                        const float* lse, float* dvec, void* dqkv, float* scratch, int B, int S, int nh, int nkv, hipStream_t st) {
     constexpr int LDS_KV = 8 * Tile<D>::BYTES + 1024;
     hipError_t e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((S + 127) / 128) * nh * B;
-    const unsigned grid_kv = (unsigned)((S + 127) / 128) * nkv * B;
+    const int hs = dkv_head_slices(B, S, nh, nkv);
+    if (hs > 1 && !scratch) return hipErrorInvalidValue;
+    const unsigned grid_kv = (unsigned)((S + 127) / 128) * nkv * hs * B;
     const long rows = (long)B * S * nh;
     k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
     if (split_keys(grid, S)) {
@@ -676,7 +757,11 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
                                                          (bf16_t*)dqkv, S, nh, nkv, B);
     }
     k_attn_bwd_dkv<D><<<grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
-                                                          dvec, (bf16_t*)dqkv, S, nh, nkv, B);
+                                                          dvec, (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch);
+    if (hs > 1) {
+        const long n = (long)B * S * (nkv * D / 4);
+        k_attn_dkv_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(scratch, hs, (long)B * S, nkv * D, (bf16_t*)dqkv, ld, nh * D);
+    }
     return hipGetLastError();
 }
 
@@ -689,12 +774,12 @@ hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, in
 }
 
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                         void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st) {
+                         void* dqkv, float* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st) {
     const long bytes = (long)B * S * ld * 2;
     const long do_bytes = (long)B * S * nh * d * 2;
     if (bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
-    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, nkv, st);
-    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, B, S, nh, nkv, st);
+    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, scratch, B, S, nh, nkv, st);
+    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, scratch, B, S, nh, nkv, st);
     return hipErrorInvalidValue;
 }
 

@@ -20,7 +20,8 @@ hipError_t gemm_bf16(const GemmDesc& g, hipStream_t st);
 hipError_t gemm_f32(const GemmDesc& g, hipStream_t st);
 hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st);
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                         void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st);
+                         void* dqkv, float* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st);
+size_t attn_bf16_bwd_scratch_bytes(int B, int S, int nh, int nkv, int d);
 hipError_t attn_f32_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st);
 hipError_t attn_f32_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
                         void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st);
@@ -31,9 +32,12 @@ hipError_t gemm(int dtype, const GemmDesc& g, hipStream_t st) {
 hipError_t attn_fwd(int dtype, const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st) {
     return dtype == DT_BF16 ? attn_bf16_fwd(qkv, ld, o, lse, B, S, nh, nkv, d, st) : attn_f32_fwd(qkv, ld, o, lse, B, S, nh, nkv, d, st);
 }
+size_t attn_bwd_scratch_bytes(int dtype, int B, int S, int nh, int nkv, int d) {
+    return dtype == DT_BF16 ? attn_bf16_bwd_scratch_bytes(B, S, nh, nkv, d) : 0;
+}
 hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                    void* dqkv, int B, int S, int nh, int nkv, int d, hipStream_t st) {
-    return dtype == DT_BF16 ? attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, nkv, d, st)
+                    void* dqkv, void* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st) {
+    return dtype == DT_BF16 ? attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, (float*)scratch, B, S, nh, nkv, d, st)
                             : attn_f32_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, nkv, d, st);
 }
 }  // namespace hh
@@ -190,7 +194,7 @@ static SavedLayout saved_layout(const Dims& d) {
 }
 
 struct WorkLayout {
-    size_t m, dgu, dhn, dh, da, dqkv, dvec, partial, gemm_ws, total;
+    size_t m, dgu, dhn, dh, da, dqkv, dvec, dkv_part, partial, gemm_ws, total;
 };
 static WorkLayout work_layout(const Dims& d) {
     WorkLayout w;
@@ -204,6 +208,7 @@ static WorkLayout work_layout(const Dims& d) {
     w.da = take(T * d.A * d.es);
     w.dqkv = take(T * d.Q3 * d.es);
     w.dvec = take((size_t)d.B * d.nh * d.S * 4);
+    w.dkv_part = take(attn_bwd_scratch_bytes(d.dt, d.B, d.S, d.nh, d.nkv, d.d));   // partial dK, dV of grouped heads
     w.partial = take((size_t)rmsnorm_bwd_blocks(d.T) * d.H * 4);
     w.gemm_ws = take(d.dt == DT_BF16 ? GEMM_WS_BYTES : 0);
     w.total = off;
@@ -451,7 +456,7 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
     const int Akv = d.Akv, Q3 = d.Q3;
     const int part_w[3] = {A, Akv, Akv}, part_c[3] = {0, A, A + Akv};
-    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, Q3, a, da, lse, dvec, dqkv, d.B, d.S, d.nh, d.nkv, d.d, st));
+    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, Q3, a, da, lse, dvec, dqkv, at(ws, wl.dkv_part), d.B, d.S, d.nh, d.nkv, d.d, st));
     TR(HH_TRACE_ELEMENTWISE, 2.0 * T * (A + Akv) * es, rope(dt, dqkv, Q3, T, d.S, d.nh + d.nkv, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
                             (const char*)w->wv == (const char*)w->wk + (size_t)Akv * H * es;

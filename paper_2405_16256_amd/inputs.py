@@ -136,6 +136,8 @@ CFG3 = LayerShape(12288, 12, 128, 4096, 4096, 1)    # 140B-class layer at a TP=8
 # Llama-2 values for that hidden size, which the paper does not state)
 SHAPE_13B = LayerShape(5120, 40, 128, 13824, 2048, 1)        # 13B-class layer: 40 x 128 heads
 SHAPE_70B_TP8 = LayerShape(8192, 8, 128, 3584, 4096, 1)      # 70B/140B-class hidden 8192 at a TP=8 share (MHA)
+SHAPE_70B_GQA_TP8 = LayerShape(8192, 8, 128, 3584, 4096, 1, n_kv_heads=1)   # same, 64 query / 8 key-value heads over TP=8
+SHAPE_70B_GQA = LayerShape(8192, 64, 128, 28672, 4096, 1, n_kv_heads=8)        # the whole hidden-8192 layer (no tensor parallelism)
 SEEDS = {"cfg1": 1001, "cfg2": 1002, "cfg3": 1003, "cfg4": 1004, "cfg5": 1005}
 
 

@@ -504,5 +504,17 @@ def test_bf16_grouped_query_attention_small_and_long(ctx):
 def test_bf16_70b_class_tp_share_with_grouped_queries_full_size(ctx):
     # Table 1's 70B / 140B hidden size with the public 64 query / 8 key-value heads at a TP=8 share: 8 local query heads
     # on one local key/value head
-    s = I.LayerShape(8192, 8, 128, 3584, 4096, 1, n_kv_heads=1)
+    s = I.SHAPE_70B_GQA_TP8
     check_layer(ctx, s, True, 76, label="h8192-gqa-tp8")
+
+
+@pytest.mark.timeout(900)
+def test_bf16_whole_hidden_8192_layer_with_grouped_queries_full_size(ctx):
+    # Table 1's hidden size 8192 without tensor parallelism: 64 query heads on 8 key/value heads, ffn 28672 (856 M parameters;
+    # the fp32 gradient of the packed gate|up weight is the largest single buffer the GEMM addresses, 1.88 GB)
+    check_layer(ctx, I.SHAPE_70B_GQA, True, 77, label="h8192-gqa-tp1")
+
+
+def test_bf16_grouped_queries_summed_inside_one_workgroup(ctx):
+    # enough (key block, key/value head, sample) jobs that each dK/dV workgroup takes both query heads of its group itself
+    check_layer(ctx, I.LayerShape(256, 16, 64, 512, 2048, 8, n_kv_heads=8), True, 78, label="gqa-heads-in-one-workgroup")
