@@ -276,9 +276,127 @@ hipError_t rmsnorm_fwd(int dtype, const void* x, const void* g, void* xn, float*
     return hipGetLastError();
 }
 
+// Rows of exactly NV * TPB * V elements: the three input rows of row r + 1 are requested before row r is
+// reduced and written, each in its own registers, so the memory queue never drains between rows.  The one
+// barrier per row waits for LDS only (a full workgroup fence would also wait for the loads in flight).
+__device__ __forceinline__ void keep_raw(uint4& v) { asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)); }
+__device__ __forceinline__ void keep_raw(float4& v) { asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)); }
+
+template <typename T, int NV>
+__global__ __launch_bounds__(TPB, 2) void k_rmsnorm_bwd_rows(const T* __restrict__ dxn, const T* __restrict__ x,
+                                                          const float* __restrict__ r, const T* __restrict__ g,
+                                                          const T* __restrict__ dres, T* __restrict__ dx,
+                                                          float* __restrict__ partial, int T_rows, int rpb) {
+    constexpr int V = Vec<T>::N;
+    constexpr int H = NV * TPB * V;
+    typedef typename Vec<T>::Raw Raw;
+    extern __shared__ float colacc[];  // [H]
+    __shared__ float red[2][NWAVES];
+    struct Row { Raw d[NV], x[NV], res[NV]; float rs; };
+    auto fetch = [&](Row& w, int row) {
+        const size_t base = (size_t)row * H;
+#pragma unroll
+        for (int i = 0; i < NV; i++) {
+            const int c = (threadIdx.x + i * TPB) * V;
+            w.d[i] = Vec<T>::raw(dxn + base + c);
+            w.x[i] = Vec<T>::raw(x + base + c);
+            w.res[i] = Vec<T>::raw(dres + base + c);
+        }
+        w.rs = r[row];
+    };
+    Raw gain[NV];
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+        const int c = (threadIdx.x + i * TPB) * V;
+        gain[i] = Vec<T>::raw(g + c);
+#pragma unroll
+        for (int e = 0; e < V; e++) colacc[c + e] = 0.f;   // only this thread ever touches these columns
+    }
+    const int row0 = blockIdx.x * rpb;
+    const int row1 = min(T_rows, row0 + rpb);
+    const float invH = 1.0f / (float)H;
+    const int wave = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+    auto finish = [&](Row& w, int row) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; i++) {
+            float d[V], xx[V], gg[V];
+            Vec<T>::widen(w.d[i], d);
+            Vec<T>::widen(w.x[i], xx);
+            Vec<T>::widen(gain[i], gg);
+#pragma unroll
+            for (int e = 0; e < V; e++) s += d[e] * gg[e] * xx[e];
+        }
+        s = wave_sum(s);
+        float* rd = red[row & 1];      // the other parity's readers are a barrier behind at most
+        if (lane == 0) rd[wave] = s;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        float tot = 0.f;
+#pragma unroll
+        for (int i = 0; i < NWAVES; i++) tot += rd[i];
+        // the raw rows are unpacked a second time below: keeping the fp32 copies of the first pass alive
+        // across the barrier would double the registers a row takes
+#pragma unroll
+        for (int i = 0; i < NV; i++) { keep_raw(w.d[i]); keep_raw(w.x[i]); }
+        const float rs = w.rs;
+        const float c1 = tot * rs * invH;  // mean_j(w_j u_j)
+        const size_t base = (size_t)row * H;
+#pragma unroll
+        for (int i = 0; i < NV; i++) {
+            const int c = (threadIdx.x + i * TPB) * V;
+            float d[V], xx[V], gg[V], rr[V], o[V];
+            Vec<T>::widen(w.d[i], d);
+            Vec<T>::widen(w.x[i], xx);
+            Vec<T>::widen(gain[i], gg);
+            Vec<T>::widen(w.res[i], rr);
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                const float u = xx[e] * rs;
+                colacc[c + e] += d[e] * u;
+                o[e] = rr[e] + rs * (d[e] * gg[e] - u * c1);
+            }
+            Vec<T>::store(dx + base + c, o);
+        }
+    };
+    if (row0 >= row1) return;
+    // fetches past the block's last row re-read that row (in bounds, unused): no branch around a request
+    const int last = row1 - 1;
+    Row a, b;
+    fetch(a, row0);
+    for (int row = row0; row < row1; row += 2) {
+        fetch(b, min(row + 1, last));
+        finish(a, row);
+        fetch(a, min(row + 2, last));
+        if (row + 1 < row1) finish(b, row + 1);
+    }
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+        const int c = (threadIdx.x + i * TPB) * V;
+#pragma unroll
+        for (int e = 0; e < V; e++) partial[(size_t)blockIdx.x * H + c + e] = colacc[c + e];
+    }
+}
+
+template <typename T, int NV>
+static hipError_t launch_rmsnorm_bwd_rows(const void* dxn, const void* x, const float* r, const void* g, const void* dres,
+                                          void* dx, float* partial, int T_rows, int rpb, int nblk, hipStream_t st) {
+    constexpr int lds = NV * TPB * Vec<T>::N * (int)sizeof(float);
+    static bool attr_set = false;
+    if (lds > 48 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_rmsnorm_bwd_rows<T, NV>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    k_rmsnorm_bwd_rows<T, NV><<<nblk, TPB, lds, st>>>((const T*)dxn, (const T*)x, r, (const T*)g, (const T*)dres, (T*)dx,
+                                                      partial, T_rows, rpb);
+    return hipGetLastError();
+}
+
 static inline int rms_rows_per_block(int T) {
     int rpb = 8;
-    while ((T + rpb - 1) / rpb > 512) rpb *= 2;
+    while ((T + rpb - 1) / rpb > 256) rpb *= 2;
     return rpb;
 }
 int rmsnorm_bwd_blocks(int T) {
@@ -292,6 +410,16 @@ hipError_t rmsnorm_bwd(int dtype, const void* dxn, const void* x, const float* r
     const int nblk = (T + rpb - 1) / rpb;
     const size_t lds = (size_t)H * sizeof(float);
     hipError_t e;
+    if (dtype == DT_BF16 && H % (TPB * 8) == 0 && H / (TPB * 8) <= RC) {
+        switch (H / (TPB * 8)) {   // row length as a compile-time multiple of the workgroup's 16-byte vectors
+            case 1: return launch_rmsnorm_bwd_rows<bf16_t, 1>(dxn, x, r, g, dres, dx, partial, T, rpb, nblk, st);
+            case 2: return launch_rmsnorm_bwd_rows<bf16_t, 2>(dxn, x, r, g, dres, dx, partial, T, rpb, nblk, st);
+            case 3: return launch_rmsnorm_bwd_rows<bf16_t, 3>(dxn, x, r, g, dres, dx, partial, T, rpb, nblk, st);
+            case 4: return launch_rmsnorm_bwd_rows<bf16_t, 4>(dxn, x, r, g, dres, dx, partial, T, rpb, nblk, st);
+            case 5: return launch_rmsnorm_bwd_rows<bf16_t, 5>(dxn, x, r, g, dres, dx, partial, T, rpb, nblk, st);
+            default: return launch_rmsnorm_bwd_rows<bf16_t, 6>(dxn, x, r, g, dres, dx, partial, T, rpb, nblk, st);
+        }
+    }
     if (dtype == DT_BF16) {
         if (lds > 48 * 1024) {
             e = hipFuncSetAttribute((const void*)k_rmsnorm_bwd<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
