@@ -486,20 +486,19 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     const i32x4 rswdo = make_rsrc_words(dout, do_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const typename TL::Offsets offs = TL::offsets();
-    // work items: for each of the G query heads, the query tiles from the key block's diagonal to the end
+    // work items: for each of the G query heads, the query tiles from the key block's diagonal to the end;
+    // an item is (query head h, step s) with its 64 queries starting at kb*128 + 64*s
     const int nsteps = (S - kb * 128 + 63) / 64, nitems = G * nsteps;
-    auto head_of = [&](int it) { return h_first + it / nsteps; };
-    auto tile_of = [&](int it) { return kb * 128 + (it % nsteps) * 64; };
-    auto issue = [&](int st, int it) {
-        const int h = head_of(it), q = tile_of(it);
+    auto issue = [&](int st, int h, int sq) {
+        const int q = kb * 128 + sq * 64;
         TL::template dma<NW>(lds0 + st * STAGE, rsw, tokb + q, ld, h * D);
         TL::template dma<NW>(lds0 + st * STAGE + TL::BYTES, rswdo, tokb + q, A, h * D);
     };
-    // lse (log2 domain) and delta of the 64 queries of item it: thread i < 64 -> lse, 64 <= i < 128 -> delta
-    auto stat = [&](int it) -> float {
-        const int i = threadIdx.x & 63, qq = tile_of(it) + i;
+    // lse (log2 domain) and delta of the 64 queries of an item: thread i < 64 -> lse, 64 <= i < 128 -> delta
+    auto stat = [&](int h, int sq) -> float {
+        const int i = threadIdx.x & 63, qq = kb * 128 + sq * 64 + i;
         if (threadIdx.x >= 128 || qq >= S) return 0.f;
-        const size_t at = ((size_t)b * nh + head_of(it)) * S + qq;
+        const size_t at = ((size_t)b * nh + h) * S + qq;
         return threadIdx.x < 64 ? lse[at] * LOG2E : dvec[at];
     };
     // K, V of keys kb*128 .. +127: resident for the whole kernel (first wait_dma below covers them)
@@ -508,8 +507,10 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
         TL::template dma<NW>(lds0 + 2 * STAGE + i * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + hk * D);
         TL::template dma<NW>(lds0 + 2 * STAGE + (2 + i) * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + (nkv + hk) * D);
     }
-    issue(0, 0);
-    float nstat = stat(0);
+    issue(0, h_first, 0);
+    float nstat = stat(h_first, 0);
+    int cs = 0;                                            // step of the item being worked on
+    int ih = nsteps > 1 ? h_first : h_first + 1, is = nsteps > 1 ? 1 : 0;   // the item after it
     const char* sKw = sKV + (kw >> 1) * TL::BYTES;        // tile holding this wave's 32 keys (row block kw & 1)
     const char* sVw = sKw + 2 * TL::BYTES;
     const float sc = 1.0f / sqrtf((float)D);
@@ -520,12 +521,12 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
 #pragma unroll
         for (int r = 0; r < 16; r++) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-    for (int t = 0; t < nitems; t++) {
-        const int qt = tile_of(t);
+    for (int t = 0; t < nitems; t++, cs = is, ih += (is + 1 == nsteps), is = (is + 1 == nsteps) ? 0 : is + 1) {
+        const int qt = kb * 128 + cs * 64;
         if (threadIdx.x < 128) sLD[(t & 1) * 128 + threadIdx.x] = nstat;   // lse / delta of item t (fetched a step ago)
         wait_dma();
         __syncthreads();   // item t and its lse/delta are in LDS for everyone; everyone has finished with item t-1
-        if (t + 1 < nitems) { issue((t + 1) & 1, t + 1); nstat = stat(t + 1); }
+        if (t + 1 < nitems) { issue((t + 1) & 1, ih, is); nstat = stat(ih, is); }
         const char* sQ = smem + (t & 1) * STAGE;
         const char* sO = sQ + TL::BYTES;
         const float* sL = sLD + (t & 1) * 128;
