@@ -518,3 +518,55 @@ def test_bf16_whole_hidden_8192_layer_with_grouped_queries_full_size(ctx):
 def test_bf16_grouped_queries_summed_inside_one_workgroup(ctx):
     # enough (key block, key/value head, sample) jobs that each dK/dV workgroup takes both query heads of its group itself
     check_layer(ctx, I.LayerShape(256, 16, 64, 512, 2048, 8, n_kv_heads=8), True, 78, label="gqa-heads-in-one-workgroup")
+
+
+def test_stage_step_recorded_in_a_graph_replays_bit_identically(ctx):
+    # callers may record the stage step into a HIP graph (no allocation, host synchronisation or memset happens inside once
+    # the context is warm); every replay, with eager work and synchronisations in between, must give the eager result bit for bit
+    s, k, M = I.LayerShape(512, 8, 64, 768, 300, 2, n_kv_heads=2), 2, 3
+    say("[case] graph replay shape=%s k=%d M=%d" % (s, k, M))
+    cfg = L.cfg_of(s, True)
+    ws_np = [I.layer_weights(91, l, s, True) for l in range(k)]
+    acts = [I.activations(91, s, m, True) for m in range(M)]
+    layers = [L.DeviceLayer(w, s, True) for w in ws_np]
+    xs = [L.to_dev(a[0], True) for a in acts]
+    dys = [L.to_dev(a[1], True) for a in acts]
+    ys = [torch.empty_like(t) for t in xs]
+    dxs = [torch.empty_like(t) for t in xs]
+    pool_b, wsb = hh.hh_stage_sizes(cfg, k, M)
+    pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
+    wsp = torch.empty(wsb, dtype=torch.uint8, device=L.DEV)
+    wst, gst = [l.wstruct for l in layers], [l.gstruct for l in layers]
+
+    def step():
+        hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 1, pool, wsp, L.stream_ptr())
+
+    step()
+    torch.cuda.synchronize()
+    want_y = [t.clone() for t in ys]
+    want_dx = [t.clone() for t in dxs]
+    want_g = [{n: v.copy() for n, v in l.grads_np().items()} for l in layers]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in ys + dxs:
+            t.fill_(float("nan"))
+        for l in layers:
+            for t in l.g.values():
+                t.fill_(7.0)                     # zero_grads_first: the replay must not depend on what the buffers held
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for m in range(M):
+            assert torch.equal(ys[m], want_y[m]) and torch.equal(dxs[m], want_dx[m]), (rep, m)
+        for l, wg in zip(layers, want_g):
+            got = l.grads_np()
+            for n in I.WEIGHT_NAMES:
+                assert np.array_equal(got[n], wg[n]), (rep, n)
+        step()                                   # eager work between replays
+        torch.cuda.synchronize()
