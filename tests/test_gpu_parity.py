@@ -570,3 +570,33 @@ def test_stage_step_recorded_in_a_graph_replays_bit_identically(ctx):
                 assert np.array_equal(got[n], wg[n]), (rep, n)
         step()                                   # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_forward_without_saved_block_and_backward_writing_over_dy(ctx):
+    # two conventions of the boundary: saved == NULL runs the forward alone (the workspace then also holds the saved
+    # block), and dx may be the buffer dy came in
+    s = I.LayerShape(512, 8, 64, 768, 333, 2, n_kv_heads=4)
+    say("[case] forward-only and dx aliasing dy, shape=%s" % (s,))
+    cfg = L.cfg_of(s, True)
+    w = I.layer_weights(93, 0, s, True)
+    x_np, dy_np = I.activations(93, s, 0, True)
+    layer = L.DeviceLayer(w, s, True)
+    y_ref, dx_ref, _ = L.run_layer(ctx, s, True, layer, x_np, dy_np)
+    g_ref = {n: v.copy() for n, v in layer.grads_np().items()}
+    saved_b, ws_b = hh.hh_layer_sizes(cfg)
+    x = L.to_dev(x_np, True)
+    y = torch.empty_like(x)
+    big_ws = torch.empty(saved_b + ws_b, dtype=torch.uint8, device=L.DEV)
+    hh.hh_layer_fwd(ctx, cfg, layer.wstruct, x, y, None, big_ws, L.stream_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(L.to_np(y), y_ref)
+    saved = torch.empty(saved_b, dtype=torch.uint8, device=L.DEV)
+    ws = torch.empty(ws_b, dtype=torch.uint8, device=L.DEV)
+    dy = L.to_dev(dy_np, True)
+    hh.hh_layer_fwd(ctx, cfg, layer.wstruct, x, y, saved, ws, L.stream_ptr())
+    hh.hh_layer_bwd(ctx, cfg, layer.wstruct, x, saved, dy, dy, layer.gstruct, 0, ws, L.stream_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(L.to_np(dy), dx_ref)
+    got = layer.grads_np()
+    for n in I.WEIGHT_NAMES:
+        assert np.array_equal(got[n], g_ref[n]), n
