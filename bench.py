@@ -64,7 +64,7 @@ def main():
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic) for scaling rocprofv3 byte counters")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % a.gpus,
+        print("bench.py: the library runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % a.gpus,
               file=sys.stderr)
         sys.exit(2)
 

@@ -2,6 +2,9 @@
 // buffer resources, wave reductions.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdint>
 #include <stdint.h>
 
 namespace hh {
@@ -65,6 +68,21 @@ template <> struct Vec<bf16_t> {
 // ---- buffer resources: out-of-range loads return 0, stores are dropped ------
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// ---- dynamic LDS above the 48 KB default -------------------------------------
+// The limit is an attribute of the (kernel, device) pair.  `done` is the calling launcher's own record (one
+// bit per device, one record per kernel instantiation) of where it has been raised already.
+inline hipError_t allow_lds(const void* kern, int bytes, std::atomic<uint64_t>& done) {
+    if (bytes <= 48 * 1024) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_relaxed) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_relaxed);
+    return e;
 }
 
 // ---- wave / block reductions -----------------------------------------------

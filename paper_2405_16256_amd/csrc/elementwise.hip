@@ -383,12 +383,9 @@ template <typename T, int NV>
 static hipError_t launch_rmsnorm_bwd_rows(const void* dxn, const void* x, const float* r, const void* g, const void* dres,
                                           void* dx, float* partial, int T_rows, int rpb, int nblk, hipStream_t st) {
     constexpr int lds = NV * TPB * Vec<T>::N * (int)sizeof(float);
-    static bool attr_set = false;
-    if (lds > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_rmsnorm_bwd_rows<T, NV>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    const hipError_t e = allow_lds((const void*)k_rmsnorm_bwd_rows<T, NV>, lds, lds_ok);
+    if (e != hipSuccess) return e;
     k_rmsnorm_bwd_rows<T, NV><<<nblk, TPB, lds, st>>>((const T*)dxn, (const T*)x, r, (const T*)g, (const T*)dres, (T*)dx,
                                                       partial, T_rows, rpb);
     return hipGetLastError();

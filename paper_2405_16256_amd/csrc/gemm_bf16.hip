@@ -219,13 +219,10 @@ __global__ __launch_bounds__(GTHREADS) void k_gemm_bf16(const bf16_t* __restrict
 template <int KIND, int BM, int BN, bool OUT_F32>
 static hipError_t launch(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
     constexpr int LDS = 2 * (BM + BN) * GK * 2;
-    static bool attr_set = false;
+    static std::atomic<uint64_t> lds_ok{0};
     auto kern = k_gemm_bf16<KIND, BM, BN, OUT_F32>;
-    if (LDS > 48 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const hipError_t e = allow_lds((const void*)kern, LDS, lds_ok);
+    if (e != hipSuccess) return e;
     const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
     kern<<<tiles, GTHREADS, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
                                        (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate);
@@ -549,13 +546,10 @@ constexpr int NUM_CU = 256;
 template <int KIND, bool OUT_F32>
 static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
     constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES + 8 * 4096;   // two stages + the epilogue patches of the 8 waves
-    static bool attr_set = false;
+    static std::atomic<uint64_t> lds_ok{0};
     auto kern = k_gemm_dma<KIND, OUT_F32>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const hipError_t e = allow_lds((const void*)kern, LDS, lds_ok);
+    if (e != hipSuccess) return e;
     const int tiles = ((g.M + DTILE - 1) / DTILE) * ((g.N + DTILE - 1) / DTILE);
     const int nk = (g.K + DK - 1) / DK;
     int full = tiles, tail = 0, ksplit = 1;

@@ -123,12 +123,20 @@ static int check_cfg(const hh_layer_cfg* c) {
     if (c->hidden % mult || A % mult || c->ffn % mult)
         return fail(HH_ERR_UNSUPPORTED_SHAPE, "hidden, n_heads*head_dim and ffn must be multiples of %d for this dtype", mult);
     if (c->hidden > 32768) return fail(HH_ERR_UNSUPPORTED_SHAPE, "hidden %d exceeds 32768", c->hidden);
+    // The kernels address every buffer with 32-bit byte offsets: outputs below 2^31 bytes, GEMM operands below
+    // 2^32 - 2^25.  Packed q|k|v and gate|up gradients that would be larger are written part by part (see the
+    // backward), so only the single projections bound the fp32 gradients.
+    const long es = c->dtype == HH_BF16 ? 2 : 4;
     const long T = (long)c->seq * c->micro_batch;
-    const long lim = (1L << 31) - (1L << 25);
-    const long wide = std::max<long>(std::max<long>(c->hidden, 3 * A), 2L * c->ffn);
+    const long Q3 = A + 2L * c->n_kv_heads * c->head_dim;
+    const long wide = std::max<long>(std::max<long>(c->hidden, Q3), 2L * c->ffn);
     if (wide > 65535) return fail(HH_ERR_UNSUPPORTED_SHAPE, "a row of %ld elements exceeds 65535", wide);
-    if (T * wide >= lim || (long)c->hidden * std::max<long>(3 * A, 2L * c->ffn) >= lim)
-        return fail(HH_ERR_UNSUPPORTED_SHAPE, "a tensor would reach 2^31 elements");
+    if (T * wide * es >= (1L << 31))
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "an activation of %ld x %ld elements reaches 2^31 bytes", T, wide);
+    if ((long)c->hidden * std::max<long>(A, c->ffn) * 4 >= (1L << 31))
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "the fp32 gradient of one projection reaches 2^31 bytes");
+    if ((long)c->hidden * wide * es >= (1L << 32) - (1L << 25))
+        return fail(HH_ERR_UNSUPPORTED_SHAPE, "a packed weight of %d x %ld elements reaches 2^32 bytes", c->hidden, wide);
     return HH_OK;
 }
 
@@ -435,7 +443,7 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     TR(HH_TRACE_ELEMENTWISE, 6.0 * T * F * es, swiglu_bwd(dt, m, gu, dgu, m, T, F, st));                                          // dgate|dup, m
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, H, F, T, dy, H, m, F, g->w_down, F, nullptr, 0, 1, acc), st));
     const bool gu_packed = (const char*)w->w_up == (const char*)w->w_gate + (size_t)F * H * es;
-    const bool dgu_packed = (char*)g->w_up == (char*)g->w_gate + (size_t)F * H * 4;
+    const bool dgu_packed = (char*)g->w_up == (char*)g->w_gate + (size_t)F * H * 4 && (size_t)2 * F * H * 4 < ((size_t)1 << 31);
     if (dgu_packed) {
         HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, 2 * F, H, T, dgu, 2 * F, hn, H, g->w_gate, H, nullptr, 0, 1, acc), st));
     } else {
@@ -460,7 +468,8 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     TR(HH_TRACE_ELEMENTWISE, 2.0 * T * (A + Akv) * es, rope(dt, dqkv, Q3, T, d.S, d.nh + d.nkv, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
                             (const char*)w->wv == (const char*)w->wk + (size_t)Akv * H * es;
-    const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)Akv * H * 4;
+    const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)Akv * H * 4 &&
+                             (size_t)Q3 * H * 4 < ((size_t)1 << 31);
     if (dqkv_packed) {
         HIP_TRY(tgemm(ctx, dt, desc(GEMM_TN, Q3, H, T, dqkv, Q3, xn, H, g->wq, H, nullptr, 0, 1, acc), st));
     } else {

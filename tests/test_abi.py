@@ -76,6 +76,10 @@ def test_sizes():
     (dict(dtype=7), hh.HH_ERR_INVALID_ARG),
     (dict(rope_base=0.0), hh.HH_ERR_INVALID_ARG),
     (dict(seq=1 << 20), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    # byte extents the kernels' 32-bit offsets cannot reach: a [T, 2*ffn] bf16 activation of 2^31 bytes, the fp32
+    # gradient of one projection of 2^31 bytes
+    (dict(seq=32768, ffn=16384), hh.HH_ERR_UNSUPPORTED_SHAPE),
+    (dict(hidden=16384, n_heads=128, ffn=32768, seq=128), hh.HH_ERR_UNSUPPORTED_SHAPE),
 ])
 def test_cfg_validation(kw, code):
     base = dict(hidden=4096, n_heads=32, head_dim=128, ffn=11008, seq=2048, micro_batch=1)
@@ -84,6 +88,13 @@ def test_cfg_validation(kw, code):
         hh.hh_layer_sizes(hh.make_cfg(**base))
     assert e.value.code == code
     assert hh.hh_last_error() != ""
+
+
+def test_largest_accepted_extents():
+    # just below the limits: T x 2*ffn bf16 of 2^31 - 2^16 bytes; a packed gate|up gradient above 2^31 bytes is fine
+    # (it is written as two projections): hidden 12288 with ffn 28672 gives 2.8e9 bytes
+    hh.hh_layer_sizes(hh.make_cfg(4096, 32, 128, 16384 - 64, 32768 - 64, 1))
+    hh.hh_layer_sizes(hh.make_cfg(12288, 96, 128, 28672, 256, 1, n_kv_heads=8))
 
 
 def test_fp32_accepts_multiples_of_8_bf16_does_not():
