@@ -600,3 +600,35 @@ def test_forward_without_saved_block_and_backward_writing_over_dy(ctx):
     got = layer.grads_np()
     for n in I.WEIGHT_NAMES:
         assert np.array_equal(got[n], g_ref[n]), n
+
+
+def test_bf16_seeded_random_small_shapes(ctx):
+    # a sweep of small shapes drawn from a fixed seed: ragged sequence lengths around the 64- and 128-row tiles, several
+    # samples, both head sizes, grouped and plain heads, packed and separate weights
+    rng = np.random.RandomState(20240531)
+    for case in range(14):
+        d = int(rng.choice([64, 128]))
+        nkv = int(rng.choice([1, 2, 3]))
+        group = int(rng.choice([1, 1, 2, 4]))
+        nh = nkv * group
+        hidden = 64 * int(rng.randint(1, 9))
+        ffn = 64 * int(rng.randint(1, 9))
+        seq = int(rng.choice([1, 2, 31, 63, 64, 65, 127, 128, 129, 191, 257, 300]))
+        mb = int(rng.choice([1, 1, 2, 3]))
+        s = I.LayerShape(hidden, nh, d, ffn, seq, mb, n_kv_heads=nkv)
+        check_layer(ctx, s, True, 300 + case, packed=bool(case % 3), label="random-%d" % case)
+
+
+def test_fp32_seeded_random_small_shapes(ctx):
+    # the fp32 path takes any multiple of 8 for hidden, ffn and n_heads * head_dim
+    rng = np.random.RandomState(77)
+    for case in range(8):
+        d = int(rng.choice([64, 128]))
+        nkv = int(rng.choice([1, 2]))
+        nh = nkv * int(rng.choice([1, 2, 3]))
+        hidden = 8 * int(rng.randint(1, 30))
+        ffn = 8 * int(rng.randint(1, 30))
+        seq = int(rng.choice([1, 7, 33, 64, 65, 100]))
+        mb = int(rng.choice([1, 2, 3]))
+        s = I.LayerShape(hidden, nh, d, ffn, seq, mb, n_kv_heads=nkv)
+        check_layer(ctx, s, False, 400 + case, packed=bool(case % 2), label="random-f32-%d" % case)
