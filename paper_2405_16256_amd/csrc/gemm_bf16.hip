@@ -239,6 +239,10 @@ constexpr int DK = 64;           // k per stage
 constexpr int DSTAGES = 2;
 constexpr int DTILE = 256;
 constexpr int DSTAGE_BYTES = DTILE * DK * 2;   // one operand, one stage: 32 KB
+// Of the 8 DMA instructions a wave issues per stage, the last DMA_LATE wait until k step 0 of the next stage
+// (their buffer is free from the barrier on and the data is not needed before the next barrier): spreading the
+// requests measured 1.2 % faster on a whole layer than issuing all 8 during k step 3; more, or later, was slower.
+constexpr int DMA_LATE = 3;
 
 __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, i32x4 rs) {
     // each lane moves 16 bytes from (rs.base + voff) to LDS byte (lds_addr + 16*lane); lanes past the
@@ -376,6 +380,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
             const char* nA = smem + ((kt + 1) & 1) * (2 * DSTAGE_BYTES);
             const char* nB = nA + DSTAGE_BYTES;
             const bool more = kt + 2 < nk;
+            const bool late = kt >= 1 && kt + 1 < nk;   // k tile kt+1's last DMA instructions are still to be issued
             SB();
             // k steps 0..2 of tile kt: MFMAs on one fragment set while the next one is fetched
 #pragma unroll
@@ -391,6 +396,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
                     if (i == 0) { na[0] = DA::frag(cA, wm, kk + 1); nb[0] = DB::frag(cB, wn, kk + 1); nb[1] = DB::frag(cB, wn + 32, kk + 1); }
                     if (i == 1) { na[1] = DA::frag(cA, wm + 32, kk + 1); na[2] = DA::frag(cA, wm + 64, kk + 1); }
                     if (i == 2) { na[3] = DA::frag(cA, wm + 96, kk + 1); }
+                    if (kk == 0 && i < DMA_LATE && late) dma_part((kt + 1) & 1, 8 - DMA_LATE + i);
                     SB();
                 }
             }
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             SB();
-            // k step 3: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1 and issue tile kt+2
+            // k step 3: MFMAs on (a1, b1); meanwhile fetch the first fragments of tile kt+1 and issue most of tile kt+2
 #pragma unroll
             for (int i = 0; i < TM; i++) {
 #pragma unroll
@@ -408,7 +414,11 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
                 if (i == 0) { a0[0] = DA::frag(nA, wm, 0); b0[0] = DB::frag(nB, wn, 0); b0[1] = DB::frag(nB, wn + 32, 0); }
                 if (i == 1) { a0[1] = DA::frag(nA, wm + 32, 0); a0[2] = DA::frag(nA, wm + 64, 0); }
                 if (i == 2) { a0[3] = DA::frag(nA, wm + 96, 0); }
-                if (more) { dma_part(kt & 1, 2 * i); dma_part(kt & 1, 2 * i + 1); }
+                if (more) {
+#pragma unroll
+                    for (int q = 0; q < 8 - DMA_LATE; q++)
+                        if (q * 4 / (8 - DMA_LATE) == i) dma_part(kt & 1, q);
+                }
                 SB();
             }
         }
