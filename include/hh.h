@@ -109,6 +109,9 @@ typedef struct {
     uint64_t grad_bytes;           /* fp32 parameter gradients */
     uint64_t saved_act_bytes;      /* activations kept from forward to backward, per micro-batch */
     uint64_t p2p_bytes;            /* stage-boundary message, Eq. (3): micro_batch*seq*hidden*2 */
+    uint64_t workspace_bytes;      /* scratch one forward or backward pass of a layer needs (shared by all layers of a
+                                      stage): with saved_act_bytes x live micro-batches x layers it gives the stage's
+                                      activation high-water mark */
 } hh_profile_rec;
 
 typedef struct hh_ctx hh_ctx;      /* opaque: device id, rotary table */

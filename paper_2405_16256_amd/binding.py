@@ -51,7 +51,8 @@ class hh_profile_rec(C.Structure):
     _fields_ = [("layer", C.c_int32), ("fwd_ms", C.c_float), ("bwd_ms", C.c_float), ("fwd_flop", C.c_double),
                 ("bwd_flop", C.c_double), ("fwd_tflops", C.c_float), ("bwd_tflops", C.c_float),
                 ("weight_bytes", C.c_uint64), ("grad_bytes", C.c_uint64), ("saved_act_bytes", C.c_uint64),
-                ("p2p_bytes", C.c_uint64)]
+                ("p2p_bytes", C.c_uint64),
+                ("workspace_bytes", C.c_uint64)]
 
 
 class hh_trace_sum(C.Structure):

@@ -677,6 +677,7 @@ extern "C" int hh_layer_profile(hh_ctx* ctx, const hh_layer_cfg* cfg, int n_laye
         r.grad_bytes = nparam * 4;
         r.saved_act_bytes = p.saved_sz + (uint64_t)d.T * d.H * d.es;  // the saved block plus the layer's input
         r.p2p_bytes = (uint64_t)d.B * d.S * d.H * 2;
+        r.workspace_bytes = work_layout(d).total + act_bytes(d);
     }
     return HH_OK;
 }

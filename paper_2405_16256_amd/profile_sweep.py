@@ -60,7 +60,8 @@ def main() -> None:
                         "fwd_tflops": round(r0.fwd_flop / (sum(f) / k * 1e-3) / 1e12, 1),
                         "bwd_tflops": round(r0.bwd_flop / (sum(b) / k * 1e-3) / 1e12, 1),
                         "weight_bytes": r0.weight_bytes, "grad_bytes": r0.grad_bytes,
-                        "saved_act_bytes": r0.saved_act_bytes, "p2p_bytes": r0.p2p_bytes}), flush=True)
+                        "saved_act_bytes": r0.saved_act_bytes, "p2p_bytes": r0.p2p_bytes,
+                        "workspace_bytes": r0.workspace_bytes}), flush=True)
                     del pool, wsp
                 del x, dy
         del layer

@@ -419,6 +419,7 @@ def test_layer_profile_records(ctx):
         assert abs(r.fwd_tflops - f / (r.fwd_ms * 1e-3) / 1e12) < 1e-3 * r.fwd_tflops + 1e-6
         assert r.weight_bytes == 2 * nparam and r.grad_bytes == 4 * nparam
         assert r.p2p_bytes == 2 * s.micro_batch * s.seq * s.hidden      # Eq. (3)
+        assert r.workspace_bytes == hh.hh_stage_sizes(cfg, 1, 1)[1]
         assert r.saved_act_bytes > 0
     say("  profile: " + ", ".join("L%d f=%.3fms b=%.3fms" % (r.layer, r.fwd_ms, r.bwd_ms) for r in recs))
 
