@@ -15,7 +15,7 @@
 //
 // Backward is two deterministic passes (no atomics): a query-stationary pass
 // for dQ and a key-stationary pass for dK, dV, both recomputing P from the
-// saved log-sum-exp.  delta[s] = <dO[s], O[s]> comes from a small pre-pass.
+// saved log-sum-exp.  delta[s] = <dO[s], O[s]> is formed by the dQ pass and handed to the dK/dV pass.
 #include "common.h"
 #include "kernels.h"
 
@@ -304,35 +304,14 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
     }
 }
 
-// ----------------------------------------------------- delta = <dO, O> per row
-template <int D>
-__global__ __launch_bounds__(ATHREADS) void k_attn_delta(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
-                                                         float* __restrict__ dvec, int B, int S, int nh) {
-    const long w = (long)blockIdx.x * (ATHREADS / WAVE) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (w >= (long)B * S * nh) return;
-    const int h = (int)(w % nh);
-    const long tok = w / nh;
-    const int b = (int)(tok / S), s = (int)(tok % S);
-    const size_t base = (size_t)tok * nh * D + (size_t)h * D + lane * (D / 64);
-    float acc = 0.f;
-    if (D == 128) {
-        const uint32_t a = *reinterpret_cast<const uint32_t*>(o + base), g = *reinterpret_cast<const uint32_t*>(dout + base);
-        acc = lo_bf(a) * lo_bf(g) + hi_bf(a) * hi_bf(g);
-    } else {
-        acc = bf2f(o[base]) * bf2f(dout[base]);
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) dvec[((size_t)b * nh + h) * S + s] = acc;
-}
-
 // --------------------------------------------------------------- backward: dQ
 // NPAR as in k_attn_fwd: with 2, the even and the odd key tiles go to two groups of 4 waves whose dQ sums
-// are added through LDS at the end.
+// are added through LDS at the end.  The kernel also forms delta = <dO, O> of its queries (each lane holds
+// half a row of dO for the MFMAs anyway) and leaves it in dvec for the dK/dV kernel that follows.
 template <int D, int NPAR>
 __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
-                                                          const bf16_t* __restrict__ dout, uint32_t do_bytes,
-                                                          const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                          const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                          const float* __restrict__ lse, float* __restrict__ dvec,
                                                           bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
     using TL = Tile<D>;
     constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
@@ -348,6 +327,7 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
     const __amdgpu_buffer_rsrc_t rsdo = make_rsrc(dout, do_bytes);
+    const __amdgpu_buffer_rsrc_t rso = make_rsrc(o, do_bytes);
     const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const typename TL::Offsets offs = TL::offsets();
@@ -366,10 +346,22 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd
     load_qfrag<D>(dof, rsdo, tokb + query, A, h * D);
     const float sc = 1.0f / sqrtf((float)D);
     const float c = LOG2E * sc;
-    float L = 0.f, dl = 0.f;
+    // delta: this lane's half of the row, plus the other half from lane ^ 32
+    float dl = 0.f;
+    {
+        bf16x8 of[D / 16];
+        load_qfrag<D>(of, rso, tokb + query, A, h * D);
+#pragma unroll
+        for (int kk = 0; kk < D / 16; kk++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) dl = fmaf((float)dof[kk][e], (float)of[kk][e], dl);
+        dl += __shfl_xor(dl, 32, WAVE);
+    }
+    float L = 0.f;
     if (query < S) {
-        L = lse[((size_t)b * nh + h) * S + query] * LOG2E;
-        dl = dvec[((size_t)b * nh + h) * S + query];
+        const size_t at = ((size_t)b * nh + h) * S + query;
+        L = lse[at] * LOG2E;
+        if (par == 0 && hf == 0) dvec[at] = dl;
     }
     f32x16 dq[D / 32];
 #pragma unroll
@@ -742,19 +734,17 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
     const int hs = dkv_head_slices(B, S, nh, nkv);
     if (hs > 1 && !scratch) return hipErrorInvalidValue;
     const unsigned grid_kv = (unsigned)((S + 127) / 128) * nkv * hs * B;
-    const long rows = (long)B * S * nh;
-    k_attn_delta<D><<<(unsigned)((rows + 3) / 4), ATHREADS, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, B, S, nh);
     if (split_keys(grid, S)) {
         constexpr int LDS = 8 * Tile<D>::BYTES;
         e = set_lds(k_attn_bwd_dq<D, 2>, LDS);
         if (e != hipSuccess) return e;
-        k_attn_bwd_dq<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+        k_attn_bwd_dq<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)o, (const bf16_t*)dout, do_bytes, lse, dvec,
                                                              (bf16_t*)dqkv, S, nh, nkv, B);
     } else {
         constexpr int LDS = 4 * Tile<D>::BYTES;
         e = set_lds(k_attn_bwd_dq<D, 1>, LDS);
         if (e != hipSuccess) return e;
-        k_attn_bwd_dq<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+        k_attn_bwd_dq<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)o, (const bf16_t*)dout, do_bytes, lse, dvec,
                                                          (bf16_t*)dqkv, S, nh, nkv, B);
     }
     k_attn_bwd_dkv<D><<<grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
