@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
 # HBM-side bytes per GEMM call of the weight-gradient family at the default workload, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE passes over this command, scaled by a 1 GiB copy (x2.000 and x1.000): 1.029 GB fetched + 0.256 GB
 # written.  Holds for the kernel build those passes ran on; None for anything else.
-TRAFFIC_BYTES_PER_LAUNCH = {("cfg3", "gemm_tn"): 1.293e9}
+TRAFFIC_BYTES_PER_LAUNCH = {("cfg3", "gemm_tn"): 1.275e9}
 
 
 def workloads():
