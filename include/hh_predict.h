@@ -71,6 +71,20 @@ int hh_plan_layers(const hh_sim_stage *stages, int n_stages, int total_layers, i
                    int micro_batch, int seq, int hidden, int data_parallel, double flop_per_layer,
                    int slack, int32_t *layers_out, hh_sim_result *best);
 
+/* Stage order of the automatic parallel planner (Section 3.3, second rule: the stages are scheduled onto the
+ * accelerator types so that the end-to-end time is smallest, given the stage times on each type and the
+ * communication time between stages).  groups[g] describes the counts[g] identical stages that the nodes of one
+ * accelerator type form (per-layer figures as for hh_plan_layers; its link_gbytes_per_s is the link between two
+ * neighbouring stages of that group); two neighbouring stages of different groups are joined by a link of
+ * cross_link_gbytes_per_s.  A group stays contiguous in the pipeline.  Every order of the groups is tried, the
+ * layers are split for each with hh_plan_layers (same slack, same memory rule) and the order with the shortest
+ * iteration is kept; among equal times the first in lexicographic order of group indices.  n_groups <= 8.
+ * order_out: n_groups group indices in pipeline order; layers_out: one count per stage in pipeline order
+ * (sum of counts entries); both HOST.  HH_ERR_UNSUPPORTED_SHAPE when no order has a split that fits in memory. */
+int hh_plan_order(const hh_sim_stage *groups, const int32_t *counts, int n_groups, double cross_link_gbytes_per_s,
+                  int total_layers, int n_micro, int micro_batch, int seq, int hidden, int data_parallel,
+                  double flop_per_layer, int slack, int32_t *order_out, int32_t *layers_out, hh_sim_result *best);
+
 #ifdef __cplusplus
 }
 #endif

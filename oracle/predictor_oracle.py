@@ -104,3 +104,46 @@ def mfu(model_flop_per_iteration, iter_s, peaks_tflops, counts):
     n = sum(counts)
     achieved = model_flop_per_iteration / iter_s / n / 1e12
     return achieved / weighted_mean(peaks_tflops, counts)
+
+
+def compositions(total, parts):
+    """All ways to write total as an ordered sum of `parts` positive integers."""
+    if parts == 1:
+        if total >= 1:
+            yield (total,)
+        return
+    for first in range(1, total - parts + 2):
+        for rest in compositions(total - first, parts - 1):
+            yield (first,) + rest
+
+
+def best_order_and_split(groups, counts, cross_link_ms_per_msg, total_layers, n_micro):
+    """Section 3.3, both rules by exhaustion: every order of the accelerator groups along the pipeline (a group's
+    stages stay together), every split of the layers over the stages; the fastest iteration wins, the first found
+    among equals (orders in lexicographic order of group indices).  groups[g] = dict(fwd_ms, bwd_ms per layer,
+    link_ms = transfer time of one boundary tensor inside the group, weight/grad/optimizer/saved_act bytes per layer,
+    memory_bytes or 0).  Returns (order, layers, iteration_ms)."""
+    import itertools
+    best = None
+    for order in itertools.permutations(range(len(groups))):
+        stages, links = [], []
+        for k, g in enumerate(order):
+            for c in range(counts[g]):
+                stages.append(groups[g])
+                links.append(groups[g]["link_ms"] if c < counts[g] - 1 else cross_link_ms_per_msg)
+        links = links[:-1]
+        P = len(stages)
+        for layers in compositions(total_layers, P):
+            ok = True
+            for p, (st, n) in enumerate(zip(stages, layers)):
+                if st["memory_bytes"] and stage_peak_bytes(p, P, n_micro, n, st["weight_bytes"], st["grad_bytes"],
+                                                           st["optimizer_bytes"], st["saved_act_bytes"]) > st["memory_bytes"]:
+                    ok = False
+                    break
+            if not ok:
+                continue
+            it, _, _ = simulate([n * st["fwd_ms"] for n, st in zip(layers, stages)],
+                                [n * st["bwd_ms"] for n, st in zip(layers, stages)], links, n_micro)
+            if best is None or it < best[2] - 1e-12:
+                best = (list(order), list(layers), it)
+    return best

@@ -29,7 +29,7 @@ HH_BF16 = 1
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
            "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
-           "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers")
+           "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers", "hh_plan_order")
 TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
 
@@ -107,6 +107,8 @@ def _load() -> C.CDLL:
         "hh_sim_weighted_mean": [C.POINTER(C.c_double), C.POINTER(C.c_int64), i, C.POINTER(C.c_double)],
         "hh_plan_layers": [C.POINTER(hh_sim_stage), i, i, i, i, i, i, i, C.c_double, i, C.POINTER(C.c_int32),
                            C.POINTER(hh_sim_result)],
+        "hh_plan_order": [C.POINTER(hh_sim_stage), C.POINTER(C.c_int32), i, C.c_double, i, i, i, i, i, i, C.c_double, i,
+                          C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(hh_sim_result)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -270,3 +272,19 @@ def hh_plan_layers(stages: Sequence[hh_sim_stage], total_layers, n_micro, micro_
     _check(lib.hh_plan_layers(arr, n, total_layers, n_micro, micro_batch, seq, hidden, data_parallel, float(flop_per_layer), slack,
                               out, C.byref(res)))
     return list(out)[:n], res
+
+
+def hh_plan_order(groups: Sequence[hh_sim_stage], counts: Sequence[int], cross_link_gbytes_per_s, total_layers, n_micro,
+                  micro_batch, seq, hidden, data_parallel, flop_per_layer, slack=2):
+    """-> (group index per pipeline position, layers per stage in pipeline order, hh_sim_result)"""
+    n = len(groups)
+    assert len(counts) == n
+    arr = (hh_sim_stage * max(n, 1))(*groups)
+    cnt = (C.c_int32 * max(n, 1))(*counts)
+    total = max(sum(c for c in counts if c > 0), 1)
+    order = (C.c_int32 * max(n, 1))()
+    layers = (C.c_int32 * total)()
+    res = hh_sim_result()
+    _check(lib.hh_plan_order(arr, cnt, n, float(cross_link_gbytes_per_s), total_layers, n_micro, micro_batch, seq, hidden,
+                             data_parallel, float(flop_per_layer), slack, order, layers, C.byref(res)))
+    return list(order)[:n], list(layers)[:sum(counts)], res

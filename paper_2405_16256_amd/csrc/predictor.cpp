@@ -232,3 +232,48 @@ extern "C" int hh_plan_layers(const hh_sim_stage* stages, int n_stages, int tota
     *best = best_res;
     return HH_OK;
 }
+
+extern "C" int hh_plan_order(const hh_sim_stage* groups, const int32_t* counts, int n_groups, double cross_link_gbytes_per_s,
+                             int total_layers, int n_micro, int micro_batch, int seq, int hidden, int data_parallel,
+                             double flop_per_layer, int slack, int32_t* order_out, int32_t* layers_out, hh_sim_result* best) {
+    if (!groups || !counts) return fail(HH_ERR_INVALID_ARG, "groups / counts is NULL");
+    if (n_groups <= 0 || n_groups > 8) return fail(HH_ERR_INVALID_ARG, "n_groups must be in 1..8");
+    if (!order_out || !layers_out || !best) return fail(HH_ERR_INVALID_ARG, "order_out / layers_out / best is NULL");
+    long P = 0;
+    for (int g = 0; g < n_groups; g++) {
+        if (counts[g] <= 0) return fail(HH_ERR_INVALID_ARG, "counts must be positive");
+        P += counts[g];
+    }
+    if (P > 4096) return fail(HH_ERR_INVALID_ARG, "more than 4096 stages");
+    std::vector<int> perm(n_groups);
+    for (int g = 0; g < n_groups; g++) perm[g] = g;
+    std::vector<hh_sim_stage> st((size_t)P);
+    std::vector<int32_t> layers((size_t)P), best_layers;
+    std::vector<int> best_perm;
+    hh_sim_result best_res{};
+    bool found = false;
+    int first_error = HH_OK;
+    do {   // std::next_permutation walks the orders lexicographically, so the first of equal times is kept
+        size_t at = 0;
+        for (int k = 0; k < n_groups; k++) {
+            const int g = perm[k];
+            for (int c = 0; c < counts[g]; c++) {
+                st[at] = groups[g];
+                if (c == counts[g] - 1) st[at].link_gbytes_per_s = cross_link_gbytes_per_s;   // to the next group
+                at++;
+            }
+        }
+        hh_sim_result r{};
+        const int rc = hh_plan_layers(st.data(), (int)P, total_layers, n_micro, micro_batch, seq, hidden, data_parallel,
+                                      flop_per_layer, slack, layers.data(), &r);
+        if (rc == HH_ERR_UNSUPPORTED_SHAPE) continue;   // this order does not fit in memory
+        if (rc != HH_OK) { first_error = rc; break; }
+        if (!found || r.iter_ms < best_res.iter_ms) { best_res = r; best_layers = layers; best_perm = perm; found = true; }
+    } while (std::next_permutation(perm.begin(), perm.end()));
+    if (first_error != HH_OK) return first_error;
+    if (!found) return fail(HH_ERR_UNSUPPORTED_SHAPE, "no order of the groups has a layer split that fits the stages' memory");
+    for (int k = 0; k < n_groups; k++) order_out[k] = best_perm[k];
+    for (long q = 0; q < P; q++) layers_out[q] = best_layers[(size_t)q];
+    *best = best_res;
+    return HH_OK;
+}

@@ -137,3 +137,67 @@ def test_planner_respects_stage_memory():
     with pytest.raises(hh.HHError) as e:
         hh.hh_plan_layers([a_small, b_small], 9, 8, 1, 128, 256, 1, 1e9, slack=9)
     assert e.value.code == hh.HH_ERR_UNSUPPORTED_SHAPE
+
+
+# ---------------------------------------------------------------- stage order (second rule of the planner)
+def group_pair(rng, B, S, H):
+    """A library group descriptor and the oracle's view of the same group."""
+    fwd = rng.choice([1.0, 1.3, 2.0, 2.6])
+    link_gb = rng.choice([0.0, 5.0, 25.0])
+    w, g, opt, act = rng.randint(1, 50), rng.randint(1, 50), rng.randint(0, 100), rng.randint(1, 40)
+    mem = rng.choice([0, 0, 4000, 9000])
+    lib_group = stage(0, fwd, 2 * fwd, link=link_gb, w=w, g=g, opt=opt, act=act, mem=mem)
+    msg = O.p2p_bytes(B, S, H)
+    link_ms = msg / (link_gb * 1e9) * 1e3 if link_gb > 0 else 0.0
+    ora_group = dict(fwd_ms=fwd, bwd_ms=2 * fwd, link_ms=link_ms, weight_bytes=w, grad_bytes=g, optimizer_bytes=opt,
+                     saved_act_bytes=act, memory_bytes=mem)
+    return lib_group, ora_group
+
+
+def test_stage_order_matches_exhaustive_search_on_small_mixed_clusters():
+    rng = random.Random(11)
+    B, S, H = 1, 2048, 4096
+    tried = 0
+    while tried < 30:
+        n_groups = rng.randint(1, 3)
+        counts = [rng.randint(1, 2) for _ in range(n_groups)]
+        P = sum(counts)
+        total = rng.randint(P, P + 6)
+        M = rng.randint(2, 8)
+        pairs = [group_pair(rng, B, S, H) for _ in range(n_groups)]
+        cross_gb = rng.choice([0.0, 2.5, 25.0])
+        cross_ms = O.p2p_bytes(B, S, H) / (cross_gb * 1e9) * 1e3 if cross_gb > 0 else 0.0
+        want = O.best_order_and_split([o for _, o in pairs], counts, cross_ms, total, M)
+        if want is None:
+            with pytest.raises(hh.HHError) as e:
+                hh.hh_plan_order([l for l, _ in pairs], counts, cross_gb, total, M, B, S, H, 1, 1e12, slack=total)
+            assert e.value.code == hh.HH_ERR_UNSUPPORTED_SHAPE
+            continue
+        order, layers, res = hh.hh_plan_order([l for l, _ in pairs], counts, cross_gb, total, M, B, S, H, 1, 1e12, slack=total)
+        assert sorted(order) == list(range(n_groups)) and sum(layers) == total and min(layers) >= 1
+        assert res.iter_ms == pytest.approx(want[2], rel=1e-12)
+        tried += 1
+
+
+def test_stage_order_puts_the_memory_tight_type_late_and_keeps_slow_links_few():
+    # two accelerator types of equal speed; type 0 has little memory.  Under 1F1B the first stages hold the most
+    # live micro-batches, so the small-memory type must come last.
+    small = stage(0, 1.0, 2.0, w=10, g=10, opt=10, act=100, mem=4 * 30 + 2 * 4 * 100)   # 4 layers with at most 2 live micro-batches
+    big = stage(0, 1.0, 2.0, w=10, g=10, opt=10, act=100, mem=0)
+    order, layers, res = hh.hh_plan_order([small, big], [2, 2], 0.0, 16, 8, 1, 128, 256, 1, 1e9, slack=0)
+    assert order == [1, 0] and layers == [4, 4, 4, 4]
+    # one type, any count: the order is trivial and the result equals the plain layer split
+    st = [stage(0, 1.0, 2.0) for _ in range(4)]
+    want_layers, want = hh.hh_plan_layers(st, 12, 6, 1, 128, 256, 1, 1e9)
+    order, layers, res = hh.hh_plan_order([stage(0, 1.0, 2.0)], [4], 0.0, 12, 6, 1, 128, 256, 1, 1e9)
+    assert order == [0] and layers == want_layers and res.iter_ms == want.iter_ms
+
+
+def test_stage_order_argument_checks():
+    g = [stage(0, 1.0, 2.0)]
+    with pytest.raises(hh.HHError):
+        hh.hh_plan_order(g, [0], 0.0, 4, 2, 1, 128, 256, 1, 1e9)
+    with pytest.raises(hh.HHError):
+        hh.hh_plan_order(g * 9, [1] * 9, 0.0, 12, 2, 1, 128, 256, 1, 1e9)
+    with pytest.raises(hh.HHError):
+        hh.hh_plan_order(g, [3], 0.0, 2, 2, 1, 128, 256, 1, 1e9)       # fewer layers than stages
