@@ -117,6 +117,17 @@ def compositions(total, parts):
             yield (first,) + rest
 
 
+def pipeline_of_order(groups, counts, order, cross_link_ms_per_msg):
+    """The stage list and the link list of one order of the accelerator groups (Section 3.3: a group's stages stay
+    together).  Stage list: counts[g] copies of groups[g] for each g of `order` in turn.  Link p joins stages p and
+    p+1: the group's own link when both belong to the same group, the cross link where two groups meet."""
+    owner = [g for g in order for _ in range(counts[g])]
+    stages = [groups[g] for g in owner]
+    links = [groups[owner[p]]["link_ms"] if owner[p] == owner[p + 1] else cross_link_ms_per_msg
+             for p in range(len(owner) - 1)]
+    return stages, links
+
+
 def best_order_and_split(groups, counts, cross_link_ms_per_msg, total_layers, n_micro):
     """Section 3.3, both rules by exhaustion: every order of the accelerator groups along the pipeline (a group's
     stages stay together), every split of the layers over the stages; the fastest iteration wins, the first found
@@ -126,12 +137,7 @@ def best_order_and_split(groups, counts, cross_link_ms_per_msg, total_layers, n_
     import itertools
     best = None
     for order in itertools.permutations(range(len(groups))):
-        stages, links = [], []
-        for k, g in enumerate(order):
-            for c in range(counts[g]):
-                stages.append(groups[g])
-                links.append(groups[g]["link_ms"] if c < counts[g] - 1 else cross_link_ms_per_msg)
-        links = links[:-1]
+        stages, links = pipeline_of_order(groups, counts, order, cross_link_ms_per_msg)
         P = len(stages)
         for layers in compositions(total_layers, P):
             ok = True

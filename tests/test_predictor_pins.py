@@ -127,3 +127,118 @@ def test_mfu_definition():
     # 2 devices of peak 100 and 300 TFLOP/s run 4e14 flop in 1 s: 200 TFLOP/s per device over a mean peak of 200
     assert P.mfu(4e14, 1.0, [100.0, 300.0], [1, 1]) == pytest.approx(1.0)
     assert P.mfu(4e14, 2.0, [100.0, 300.0], [1, 1]) == pytest.approx(0.5)
+
+
+# ---- the exhaustive planner (Section 3.3, both rules): compositions, link placement, order choice ----------------
+
+def test_compositions_are_the_ordered_positive_splits():
+    from math import comb
+    assert list(P.compositions(4, 2)) == [(1, 3), (2, 2), (3, 1)]
+    assert list(P.compositions(3, 3)) == [(1, 1, 1)]
+    assert list(P.compositions(2, 3)) == []
+    assert list(P.compositions(5, 1)) == [(5,)]
+    for n, p in [(5, 2), (6, 3), (7, 4), (9, 5), (10, 3)]:
+        c = list(P.compositions(n, p))
+        assert len(c) == comb(n - 1, p - 1)          # stars and bars
+        assert len(set(c)) == len(c)
+        assert all(len(t) == p and sum(t) == n and min(t) >= 1 for t in c)
+
+
+def _group(tf, tb, link, mem=0, saved=0):
+    return dict(fwd_ms=tf, bwd_ms=tb, link_ms=link, weight_bytes=0, grad_bytes=0, optimizer_bytes=0,
+                saved_act_bytes=saved, memory_bytes=mem)
+
+
+def test_link_vector_of_each_group_order():
+    g = [_group(1.0, 2.0, 0.25), _group(1.0, 2.0, 0.5), _group(1.0, 2.0, 0.125)]
+    X = 7.0
+    # counts (2, 1): the pair's own link sits between its two stages, the cross link where the groups meet
+    st, ln = P.pipeline_of_order(g[:2], [2, 1], (0, 1), X)
+    assert [s is g[0] for s in st] == [True, True, False] and ln == [0.25, X]
+    st, ln = P.pipeline_of_order(g[:2], [2, 1], (1, 0), X)
+    assert [s is g[1] for s in st] == [True, False, False] and ln == [X, 0.25]
+    # counts (1, 2)
+    assert P.pipeline_of_order(g[:2], [1, 2], (0, 1), X)[1] == [X, 0.5]
+    assert P.pipeline_of_order(g[:2], [1, 2], (1, 0), X)[1] == [0.5, X]
+    # three groups, counts (2, 1, 3), order (2, 0, 1): 3 + 2 + 1 stages
+    st, ln = P.pipeline_of_order(g, [2, 1, 3], (2, 0, 1), X)
+    assert [g.index(s) for s in st] == [2, 2, 2, 0, 0, 1]
+    assert ln == [0.125, 0.125, X, 0.25, X]
+    # a single group has no cross link at all
+    assert P.pipeline_of_order(g[:1], [4], (0,), X)[1] == [0.25] * 3
+
+
+def test_position_of_the_slow_cross_link_alone_decides_the_order():
+    # Three stages of one layer each (3 layers: the only split is 1+1+1), every stage forward 1, backward 2,
+    # 3 micro-batches, free links inside a group, cross link 5.  1F1B programs:
+    #   stage 0: F0 F1 F2 B0 B1 B2   stage 1: F0 F1 B0 F2 B1 B2   stage 2: F0 B0 F1 B1 F2 B2
+    # Links (5, 0), i.e. the lone stage first:
+    #   stage 0 forwards end at 1, 2, 3.  Stage 1: F0 6-7, F1 7-8.  Stage 2: F0 7-8, B0 8-10, F1 10-11, B1 11-13.
+    #   Stage 1: B0 10-12, F2 (arrived at 8) 12-13, B1 13-15.  Stage 2: F2 13-14, B2 14-16.  Stage 1: B2 16-18.
+    #   Stage 0: B0 arrives 12+5=17, 17-19; B1 arrives 20, 20-22; B2 arrives 23, 23-25.               => 25
+    # Links (0, 5), i.e. the lone stage last:
+    #   Stage 1: F0 1-2, F1 2-3.  Stage 2: F0 arrives 7, 7-8, B0 8-10, F1 (arrived 8) 10-11, B1 11-13.
+    #   Stage 1: B0 arrives 15, 15-17; F2 17-18; B1 arrives 18, 18-20.  Stage 2: F2 arrives 23, 23-24, B2 24-26.
+    #   Stage 1: B2 arrives 31, 31-33.  Stage 0: B0 17-19, B1 20-22, B2 33-35.                        => 35
+    assert P.simulate([1.0] * 3, [2.0] * 3, [5.0, 0.0], 3)[0] == pytest.approx(25.0)
+    assert P.simulate([1.0] * 3, [2.0] * 3, [0.0, 5.0], 3)[0] == pytest.approx(35.0)
+    same = _group(1.0, 2.0, 0.0)
+    # group 0 is the pair: putting it first places the slow link last (35); the planner must turn the order round,
+    # which is not the first order it tries
+    order, layers, it = P.best_order_and_split([same, dict(same)], [2, 1], 5.0, 3, 3)
+    assert (order, layers, it) == ([1, 0], [1, 1, 1], pytest.approx(25.0))
+    # group 0 is the lone stage: the first order already has the slow link first
+    order, layers, it = P.best_order_and_split([same, dict(same)], [1, 2], 5.0, 3, 3)
+    assert (order, layers, it) == ([0, 1], [1, 1, 1], pytest.approx(25.0))
+
+
+def test_order_choice_with_a_slow_type_and_distinct_links_hand_worked():
+    # counts (1, 2), 3 layers (1+1+1), 2 micro-batches; type 0: forward 1, backward 2; type 1: forward 2, backward 4,
+    # link i between its two stages; cross link c.  Programs: stages 0, 1: F0 F1 B0 B1; stage 2: F0 B0 F1 B1.
+    # Order (0, 1), links (c, i):  stage 0 F: 1, 2.  Stage 1: F0 1+c..3+c, F1 ..5+c.  Stage 2: F0 3+c+i..5+c+i,
+    #   B0 ..9+c+i, F1 ..11+c+i, B1 ..15+c+i.  Stage 1: B0 9+c+2i..13+c+2i, B1 15+c+2i..19+c+2i.
+    #   Stage 0: B0 13+2c+2i..15+2c+2i, B1 19+2c+2i..21+2c+2i.                                => 21 + 2c + 2i
+    # Order (1, 0), links (i, c):  stage 0 F: 2, 4.  Stage 1: F0 2+i..4+i, F1 ..6+i.  Stage 2: F0 4+i+c..5+i+c,
+    #   B0 ..7+i+c, F1 ..8+i+c, B1 ..10+i+c.  Stage 1: B0 7+i+2c..11+i+2c, B1 ..15+i+2c.
+    #   Stage 0: B0 11+2i+2c..15+2i+2c, B1 ..19+2i+2c.                                        => 19 + 2c + 2i
+    c, i = 0.75, 0.125
+    groups = [_group(1.0, 2.0, 9.0), _group(2.0, 4.0, i)]      # type 0's own link (9) is never used: one stage
+    st, ln = P.pipeline_of_order(groups, [1, 2], (0, 1), c)
+    assert P.simulate([s["fwd_ms"] for s in st], [s["bwd_ms"] for s in st], ln, 2)[0] == pytest.approx(21 + 2 * c + 2 * i)
+    st, ln = P.pipeline_of_order(groups, [1, 2], (1, 0), c)
+    assert P.simulate([s["fwd_ms"] for s in st], [s["bwd_ms"] for s in st], ln, 2)[0] == pytest.approx(19 + 2 * c + 2 * i)
+    assert P.best_order_and_split(groups, [1, 2], c, 3, 2) == ([1, 0], [1, 1, 1], pytest.approx(19 + 2 * c + 2 * i))
+
+
+def test_exhaustive_planner_equals_enumeration_with_longest_path_costing():
+    # the same search written a second way: explicit stage owners, the longest-path brute force as the cost
+    rng = random.Random(11)
+    for _ in range(12):
+        ng = rng.randint(1, 3)
+        counts = [rng.randint(1, 2) for _ in range(ng)]
+        groups = [_group(rng.uniform(0.5, 2.0), rng.uniform(0.5, 4.0), rng.uniform(0.0, 0.5)) for _ in range(ng)]
+        cross, M = rng.uniform(0.0, 3.0), rng.randint(1, 4)
+        Pn = sum(counts)
+        total = Pn + rng.randint(0, 3)
+        best = None
+        for order in itertools.permutations(range(ng)):
+            owner = [g for g in order for _ in range(counts[g])]
+            link = [groups[owner[p]]["link_ms"] if owner[p] == owner[p + 1] else cross for p in range(Pn - 1)]
+            for cuts in itertools.combinations(range(1, total), Pn - 1):
+                lay = [b - a for a, b in zip((0,) + cuts, cuts + (total,))]
+                t = brute_force_makespan([n * groups[g]["fwd_ms"] for n, g in zip(lay, owner)],
+                                         [n * groups[g]["bwd_ms"] for n, g in zip(lay, owner)], link, M)
+                if best is None or t < best - 1e-12:
+                    best = t
+        assert P.best_order_and_split(groups, counts, cross, total, M)[2] == pytest.approx(best)
+
+
+def test_memory_rule_of_the_exhaustive_planner():
+    # 2 stages, 4 layers, 4 micro-batches; saved activations 10 per layer and live micro-batch: stage 0 holds 2 live
+    # micro-batches, stage 1 one.  Capacity 45: stage 0 may take at most 2 layers (2*2*10 = 40), stage 1 at most 4.
+    g = [_group(1.0, 2.0, 0.0, mem=45, saved=10)]
+    order, layers, _ = P.best_order_and_split(g, [2], 0.0, 4, 4)
+    assert layers == [2, 2]
+    g = [_group(1.0, 2.0, 0.0, mem=25, saved=10)]      # stage 0: one layer (20), stage 1: at most 2 -> 4 layers do not fit
+    assert P.best_order_and_split(g, [2], 0.0, 4, 4) is None
+    assert P.best_order_and_split(g, [2], 0.0, 3, 4)[1] == [1, 2]
