@@ -39,7 +39,8 @@
  *  - Every pointer must be 16-byte aligned (HH_ERR_MISALIGNED otherwise).
  *  - Shapes: head_dim 64 or 128; n_kv_heads divides n_heads; hidden, n_heads*head_dim
  *    and ffn multiples of 64 for HH_BF16 and multiples of 8 for HH_F32; any
- *    seq >= 1, micro_batch >= 1; each tensor below 2^31 elements
+ *    seq >= 1, micro_batch >= 1; every activation and every single fp32 gradient
+ *    below 2^31 bytes, every (packed) weight below 2^32 - 2^25 bytes
  *    (HH_ERR_UNSUPPORTED_SHAPE otherwise).
  *  - Argument validation happens before any GPU work is enqueued.
  */
@@ -133,6 +134,16 @@ int hh_layer_flops(const hh_layer_cfg *cfg, double *fwd_flop, double *bwd_flop);
  * `workspace` that one fwd or bwd call needs (contents of workspace need not
  * survive between calls).  Host arithmetic only; validates cfg. */
 int hh_layer_sizes(const hh_layer_cfg *cfg, size_t *saved_bytes, size_t *workspace_bytes);
+
+/* Where each saved tensor of hh_layer_fwd sits inside the `saved` block (byte offsets from its start; the
+ * tensors are the intermediate values of the layer equations at the top of this file).  xn, h, hn: [T, H];
+ * qkv: [T, A + 2*Akv] rows of rotated q | rotated k | v; a: [T, A]; gate_up: [T, 2F] rows of gate | up (storage
+ * dtype); lse: [B, n_heads, S] fp32, natural-log sum-exp of the scaled causal scores; r1, r2: [T] fp32, the
+ * inverse RMS of x and of h.  total equals saved_bytes of hh_layer_sizes.  Host arithmetic only. */
+typedef struct {
+    size_t xn, qkv, a, h, hn, gate_up, lse, r1, r2, total;
+} hh_saved_layout;
+int hh_saved_layout_of(const hh_layer_cfg *cfg, hh_saved_layout *out);
 
 /* Forward of one layer.  x [B,S,H] in, y [B,S,H] out (y must not alias x).
  * `saved` (>= saved_bytes) receives what backward needs besides x itself:

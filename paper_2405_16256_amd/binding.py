@@ -28,7 +28,7 @@ HH_BF16 = 1
 
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
-           "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
+           "hh_saved_layout_of", "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
            "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers", "hh_plan_order")
 TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
@@ -53,6 +53,10 @@ class hh_profile_rec(C.Structure):
                 ("weight_bytes", C.c_uint64), ("grad_bytes", C.c_uint64), ("saved_act_bytes", C.c_uint64),
                 ("p2p_bytes", C.c_uint64),
                 ("workspace_bytes", C.c_uint64)]
+
+
+class hh_saved_layout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("xn", "qkv", "a", "h", "hn", "gate_up", "lse", "r1", "r2", "total")]
 
 
 class hh_trace_sum(C.Structure):
@@ -93,6 +97,7 @@ def _load() -> C.CDLL:
         "hh_ctx_reserve": [vp, cfgp],
         "hh_layer_flops": [cfgp, C.POINTER(C.c_double), C.POINTER(C.c_double)],
         "hh_layer_sizes": [cfgp, sz, sz],
+        "hh_saved_layout_of": [cfgp, C.POINTER(hh_saved_layout)],
         "hh_layer_fwd": [vp, cfgp, wp, vp, vp, vp, vp, vp],
         "hh_layer_bwd": [vp, cfgp, wp, vp, vp, vp, vp, gp, i, vp, vp],
         "hh_stage_sizes": [cfgp, i, i, sz, sz],
@@ -174,6 +179,12 @@ def hh_layer_sizes(cfg: hh_layer_cfg) -> tuple[int, int]:
     s, w = C.c_size_t(), C.c_size_t()
     _check(lib.hh_layer_sizes(C.byref(cfg), C.byref(s), C.byref(w)))
     return s.value, w.value
+
+
+def hh_saved_layout_of(cfg: hh_layer_cfg) -> hh_saved_layout:
+    out = hh_saved_layout()
+    _check(lib.hh_saved_layout_of(C.byref(cfg), C.byref(out)))
+    return out
 
 
 def hh_stage_sizes(cfg: hh_layer_cfg, n_layers: int, n_micro: int) -> tuple[int, int]:

@@ -231,6 +231,15 @@ extern "C" int hh_layer_sizes(const hh_layer_cfg* cfg, size_t* saved_bytes, size
     return HH_OK;
 }
 
+extern "C" int hh_saved_layout_of(const hh_layer_cfg* cfg, hh_saved_layout* out) {
+    TRY(check_cfg(cfg));
+    if (!out) return fail(HH_ERR_INVALID_ARG, "out is NULL");
+    const SavedLayout s = saved_layout(dims_of(cfg));
+    out->xn = s.xn; out->qkv = s.qkv; out->a = s.a; out->h = s.h; out->hn = s.hn; out->gate_up = s.gu;
+    out->lse = s.lse; out->r1 = s.r1; out->r2 = s.r2; out->total = s.total;
+    return HH_OK;
+}
+
 static size_t act_bytes(const Dims& d) { return up256((size_t)d.T * d.H * d.es); }
 
 extern "C" int hh_stage_sizes(const hh_layer_cfg* cfg, int n_layers, int n_micro, size_t* saved_pool_bytes,
