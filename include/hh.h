@@ -58,7 +58,7 @@ typedef enum {
     HH_OK = 0,
     HH_ERR_INVALID_ARG = -1,       /* null pointer, non-positive count, bad enum */
     HH_ERR_UNSUPPORTED_SHAPE = -2, /* see "Shapes" above */
-    HH_ERR_BUFFER_TOO_SMALL = -3,
+    HH_ERR_BUFFER_TOO_SMALL = -3,  /* hh_layer_fwd_noalloc: the shape needs more scratch than the library's array holds */
     HH_ERR_MISALIGNED = -4,
     HH_ERR_DEVICE = -5             /* a HIP runtime call failed; text in hh_last_error() */
 } hh_status;
@@ -152,6 +152,19 @@ int hh_saved_layout_of(const hh_layer_cfg *cfg, hh_saved_layout *out);
  * hold saved_bytes + workspace_bytes. */
 int hh_layer_fwd(hh_ctx *ctx, const hh_layer_cfg *cfg, const hh_layer_weights *w,
                  const void *x, void *y, void *saved, void *workspace, void *stream);
+
+/* Forward of one layer for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as hh_layer_fwd(saved = NULL),
+ * bit for bit; the scratch it needs (hh_layer_sizes: saved_bytes + workspace_bytes) is taken from an array of
+ * HH_STATIC_SCRATCH_BYTES that the library holds on every GPU it is loaded on until the process ends.  The call makes
+ * no allocation and no synchronisation: the rotary table must exist already (hh_ctx_reserve with a cfg of at least
+ * this seq, same head_dim and rope_base; HH_ERR_INVALID_ARG otherwise), and a shape that needs more scratch than the
+ * array holds is refused with HH_ERR_BUFFER_TOO_SMALL before anything is enqueued.  Every call on one GPU uses that
+ * GPU's one array (nothing in it has to be cleared between calls; its contents are whatever the last call left):
+ * two calls whose work overlaps in time on the same GPU, from any context or stream, race. */
+#define HH_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+int hh_layer_fwd_noalloc(hh_ctx *ctx, const hh_layer_cfg *cfg, const hh_layer_weights *w,
+                         const void *x, void *y, void *stream);
 
 /* Backward of one layer.  x and saved as given to / written by hh_layer_fwd;
  * dy [B,S,H] in; dx [B,S,H] out (dx may alias dy).  accumulate == 0 writes the

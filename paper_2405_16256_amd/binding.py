@@ -25,10 +25,11 @@ HH_ERR_MISALIGNED = -4
 HH_ERR_DEVICE = -5
 HH_F32 = 0
 HH_BF16 = 1
+HH_STATIC_SCRATCH_BYTES = 128 << 20
 
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
-           "hh_saved_layout_of", "hh_layer_fwd", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
+           "hh_saved_layout_of", "hh_layer_fwd", "hh_layer_fwd_noalloc", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
            "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers", "hh_plan_order")
 TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
@@ -99,6 +100,7 @@ def _load() -> C.CDLL:
         "hh_layer_sizes": [cfgp, sz, sz],
         "hh_saved_layout_of": [cfgp, C.POINTER(hh_saved_layout)],
         "hh_layer_fwd": [vp, cfgp, wp, vp, vp, vp, vp, vp],
+        "hh_layer_fwd_noalloc": [vp, cfgp, wp, vp, vp, vp],
         "hh_layer_bwd": [vp, cfgp, wp, vp, vp, vp, vp, gp, i, vp, vp],
         "hh_stage_sizes": [cfgp, i, i, sz, sz],
         "hh_stage_step": [vp, cfgp, i, wp, i, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), gp, i, vp, vp, vp],
@@ -195,6 +197,10 @@ def hh_stage_sizes(cfg: hh_layer_cfg, n_layers: int, n_micro: int) -> tuple[int,
 
 def hh_layer_fwd(ctx, cfg, weights: hh_layer_weights, x, y, saved, workspace, stream=0) -> None:
     _check(lib.hh_layer_fwd(ctx, C.byref(cfg), C.byref(weights), _ptr(x), _ptr(y), _ptr(saved), _ptr(workspace), stream))
+
+
+def hh_layer_fwd_noalloc(ctx, cfg, weights: hh_layer_weights, x, y, stream=0) -> None:
+    _check(lib.hh_layer_fwd_noalloc(ctx, C.byref(cfg), C.byref(weights), _ptr(x), _ptr(y), stream))
 
 
 def hh_layer_bwd(ctx, cfg, weights: hh_layer_weights, x, saved, dy, dx, grads: hh_layer_grads, accumulate, workspace,

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libhh.so")
-SOURCES = ["hh_api.cpp", "predictor.cpp", "elementwise.hip", "gemm_f32.hip", "gemm_bf16.hip", "attn_f32.hip", "attn_bf16.hip"]
+SOURCES = ["hh_api.cpp", "predictor.cpp", "elementwise.hip", "gemm_f32.hip", "gemm_bf16.hip", "attn_f32.hip", "attn_bf16.hip", "scratch.hip"]
 # packed fp32 instructions are kept out of the generated code on purpose
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -43,6 +43,7 @@ hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const voi
 }  // namespace hh
 
 using namespace hh;
+static_assert(HH_STATIC_SCRATCH_BYTES == STATIC_SCRATCH_BYTES, "the header states the size of the library's scratch array");
 
 // ------------------------------------------------------------------ errors
 static thread_local char g_err[512] = "";
@@ -94,6 +95,15 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess) return hip_fail(e, "hipGetDeviceCount");
     if (device < 0 || device >= n) return fail(HH_ERR_DEVICE, "hh_ctx_create: no HIP device %d (%d visible)", device, n);
+    // the library's own scratch array lives at a different address on every GPU: look this GPU's up now
+    int prev = 0;
+    e = hipGetDevice(&prev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    e = hipSetDevice(device);
+    if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
+    e = static_scratch_init(device);
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
     hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false, 0u, nullptr};
     if (!c) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out of host memory");
     *out = c;
@@ -425,6 +435,27 @@ extern "C" int hh_layer_fwd(hh_ctx* ctx, const hh_layer_cfg* cfg, const hh_layer
         wsp = at(workspace, saved_layout(d).total);
     }
     return layer_fwd_impl(ctx, d, cfg, w, x, y, sv, wsp, (hipStream_t)stream);
+}
+
+extern "C" int hh_layer_fwd_noalloc(hh_ctx* ctx, const hh_layer_cfg* cfg, const hh_layer_weights* w, const void* x, void* y,
+                                    void* stream) {
+    TRY(check_cfg(cfg));
+    TRY(check_weights(w));
+    TRY(check_ptr(x, "x")); TRY(check_ptr(y, "y"));
+    if (x == y) return fail(HH_ERR_INVALID_ARG, "y must not alias x");
+    if (!ctx) return fail(HH_ERR_INVALID_ARG, "ctx is NULL");
+    // the rotary table is the one thing the ordinary forward may allocate: here it has to be there already
+    if (!(ctx->rope_table && ctx->rope_seq >= cfg->seq && ctx->rope_dim == cfg->head_dim && ctx->rope_base == cfg->rope_base))
+        return fail(HH_ERR_INVALID_ARG, "hh_layer_fwd_noalloc: no rotary table for this (seq, head_dim, rope_base): call hh_ctx_reserve first");
+    const Dims d = dims_of(cfg);
+    const size_t saved_b = saved_layout(d).total, need = saved_b + work_layout(d).total;
+    if (need > STATIC_SCRATCH_BYTES)
+        return fail(HH_ERR_BUFFER_TOO_SMALL, "hh_layer_fwd_noalloc: this shape needs %zu bytes of scratch, the library's array holds %zu",
+                    need, (size_t)STATIC_SCRATCH_BYTES);
+    void* base = static_scratch(ctx->device);
+    if (!base) return fail(HH_ERR_DEVICE, "hh_layer_fwd_noalloc: the scratch array of device %d was never looked up", ctx->device);
+    // same carving as hh_layer_fwd with saved == NULL: the saved block first, the workspace behind it
+    return layer_fwd_impl(ctx, d, cfg, w, x, y, base, at(base, saved_b), (hipStream_t)stream);
 }
 
 // ----------------------------------------------------------- layer backward

@@ -28,6 +28,11 @@ struct GemmDesc {
     size_t ws_bytes;
 };
 constexpr size_t GEMM_WS_BYTES = (size_t)64 << 20;   // enough for 256 partial tiles of 256x256 fp32
+
+// The library's own scratch array (one per GPU, held until the process ends) and its size.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)128 << 20;
+hipError_t static_scratch_init(int device);   // `device` must be current; looks the array's address up once
+void* static_scratch(int device);             // that address (null before a successful init)
 hipError_t gemm(int dtype, const GemmDesc& g, hipStream_t st);
 
 // xn = x * r * g, r = 1/sqrt(mean(x^2)+eps) per row.
