@@ -153,3 +153,51 @@ def best_order_and_split(groups, counts, cross_link_ms_per_msg, total_layers, n_
             if best is None or it < best[2] - 1e-12:
                 best = (list(order), list(layers), it)
     return best
+
+
+def plan_cluster(groups, cross_link_ms_per_msg, total_layers, global_batch, micro_batch):
+    """The whole three-level search tree of Section 3.3 by exhaustion.  groups[g] = dict(n_nodes, devices_per_node,
+    fwd_ms_tp / bwd_ms_tp / saved_act_bytes_tp: lists indexed by log2 of the tensor-parallel degree (time <= 0: not
+    profiled), link_ms, dp_ms_per_byte (ring all-reduce time per byte and device between replicas, 0: free),
+    weight_bytes / grad_bytes / optimizer_bytes per whole layer, memory_bytes or 0).
+
+    Level 2: one data-parallel degree d for every stage; level 3: one tensor-parallel degree t_g per group, inside a
+    node; every accelerator is used, so group g forms n_nodes*devices_per_node / (d*t_g) stages; level 1 under each such
+    leaf: best_order_and_split on the pipeline time.  A leaf costs that pipeline time plus the slowest stage's gradient
+    all-reduce between its d replicas, 2 (d-1)/d * grad_bytes/t * layers * dp_ms_per_byte.  The cheapest leaf wins, the
+    first found among equals (d ascending, then the t_g ascending with group 0 slowest).
+    Returns dict(d, tp, stages, order, layers, n_micro, pipeline_ms, allreduce_ms, iter_ms) or None."""
+    import itertools
+    best = None
+    max_dev = max(g["n_nodes"] * g["devices_per_node"] for g in groups)
+    for d in range(1, max_dev + 1):
+        if global_batch % (d * micro_batch):
+            continue
+        n_micro = global_batch // (d * micro_batch)
+        options = [[i for i in range(4) if g["devices_per_node"] % (1 << i) == 0 and g["fwd_ms_tp"][i] > 0 and g["bwd_ms_tp"][i] > 0]
+                   for g in groups]
+        for tp_idx in itertools.product(*options):
+            counts, stage_groups = [], []
+            for g, i in zip(groups, tp_idx):
+                t, dev = 1 << i, g["n_nodes"] * g["devices_per_node"]
+                if dev % (d * t) or dev // (d * t) < 1:
+                    break
+                counts.append(dev // (d * t))
+                stage_groups.append(dict(fwd_ms=g["fwd_ms_tp"][i], bwd_ms=g["bwd_ms_tp"][i], link_ms=g["link_ms"],
+                                         weight_bytes=g["weight_bytes"] // t, grad_bytes=g["grad_bytes"] // t,
+                                         optimizer_bytes=g["optimizer_bytes"] // t, saved_act_bytes=g["saved_act_bytes_tp"][i],
+                                         memory_bytes=g["memory_bytes"]))
+            else:
+                if sum(counts) > total_layers:
+                    continue
+                r = best_order_and_split(stage_groups, counts, cross_link_ms_per_msg, total_layers, n_micro)
+                if r is None:
+                    continue
+                order, layers, pipe = r
+                owner = [g for g in order for _ in range(counts[g])]
+                ar = max([2.0 * (d - 1) / d * (groups[g]["grad_bytes"] / (1 << tp_idx[g])) * n * groups[g]["dp_ms_per_byte"]
+                          for g, n in zip(owner, layers)] + [0.0]) if d > 1 else 0.0
+                if best is None or pipe + ar < best["iter_ms"] - 1e-12:
+                    best = dict(d=d, tp=[1 << i for i in tp_idx], stages=counts, order=order, layers=layers, n_micro=n_micro,
+                                pipeline_ms=pipe, allreduce_ms=ar, iter_ms=pipe + ar)
+    return best

@@ -30,7 +30,7 @@ HH_STATIC_SCRATCH_BYTES = 128 << 20
 WEIGHT_FIELDS = ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")
 EXPORTS = ("hh_last_error", "hh_ctx_create", "hh_ctx_destroy", "hh_ctx_reserve", "hh_layer_flops", "hh_layer_sizes",
            "hh_saved_layout_of", "hh_layer_fwd", "hh_layer_fwd_noalloc", "hh_layer_bwd", "hh_stage_sizes", "hh_stage_step", "hh_stage_step_1f1b", "hh_layer_profile", "hh_trace_begin",
-           "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers", "hh_plan_order")
+           "hh_trace_end", "hh_sim_pipeline", "hh_sim_weighted_mean", "hh_plan_layers", "hh_plan_order", "hh_plan_cluster")
 TRACE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd", "elementwise")
 
 
@@ -74,7 +74,20 @@ class hh_sim_stage(C.Structure):
 class hh_sim_result(C.Structure):
     _fields_ = [("iter_ms", C.c_double), ("bubble_fraction", C.c_double), ("tokens_per_s_per_device", C.c_double),
                 ("tflops_per_device", C.c_double), ("mean_peak_tflops", C.c_double), ("mfu", C.c_double),
-                ("n_devices", C.c_int64)]
+                ("n_devices", C.c_int64), ("search_truncated", C.c_int32), ("reserved_", C.c_int32)]
+
+
+class hh_cluster_group(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("devices_per_node", C.c_int32), ("fwd_ms_tp", C.c_double * 4), ("bwd_ms_tp", C.c_double * 4),
+                ("saved_act_bytes_tp", C.c_uint64 * 4), ("peak_tflops", C.c_double), ("link_gbytes_per_s", C.c_double),
+                ("dp_gbytes_per_s", C.c_double), ("weight_bytes", C.c_uint64), ("grad_bytes", C.c_uint64),
+                ("optimizer_bytes", C.c_uint64), ("memory_bytes", C.c_uint64)]
+
+
+class hh_cluster_plan(C.Structure):
+    _fields_ = [("data_parallel", C.c_int32), ("tensor_parallel", C.c_int32 * 8), ("stages", C.c_int32 * 8), ("order", C.c_int32 * 8),
+                ("n_stages", C.c_int32), ("n_micro", C.c_int32), ("strategies_costed", C.c_int32), ("pipeline_ms", C.c_double),
+                ("grad_allreduce_ms", C.c_double), ("sim", hh_sim_result)]
 
 
 class HHError(RuntimeError):
@@ -116,6 +129,8 @@ def _load() -> C.CDLL:
                            C.POINTER(hh_sim_result)],
         "hh_plan_order": [C.POINTER(hh_sim_stage), C.POINTER(C.c_int32), i, C.c_double, i, i, i, i, i, i, C.c_double, i,
                           C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(hh_sim_result)],
+        "hh_plan_cluster": [C.POINTER(hh_cluster_group), i, C.c_double, i, i, i, i, i, C.c_double, i, C.POINTER(hh_cluster_plan),
+                            C.POINTER(C.c_int32), i],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -305,3 +320,15 @@ def hh_plan_order(groups: Sequence[hh_sim_stage], counts: Sequence[int], cross_l
     _check(lib.hh_plan_order(arr, cnt, n, float(cross_link_gbytes_per_s), total_layers, n_micro, micro_batch, seq, hidden,
                              data_parallel, float(flop_per_layer), slack, order, layers, C.byref(res)))
     return list(order)[:n], list(layers)[:sum(counts)], res
+
+
+def hh_plan_cluster(groups: Sequence[hh_cluster_group], cross_link_gbytes_per_s, total_layers, global_batch, micro_batch, seq,
+                    hidden, flop_per_layer, slack=2, max_stages=4096):
+    """-> (hh_cluster_plan, layers per stage in pipeline order)"""
+    n = len(groups)
+    arr = (hh_cluster_group * max(n, 1))(*groups)
+    plan = hh_cluster_plan()
+    layers = (C.c_int32 * max_stages)()
+    _check(lib.hh_plan_cluster(arr, n, float(cross_link_gbytes_per_s), total_layers, global_batch, micro_batch, seq, hidden,
+                               float(flop_per_layer), slack, C.byref(plan), layers, max_stages))
+    return plan, list(layers)[:plan.n_stages]

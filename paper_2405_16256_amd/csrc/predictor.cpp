@@ -127,6 +127,8 @@ int simulate(const hh_sim_stage* st, const int32_t* layers, int P, int M, int mi
     out->tflops_per_device = flop_per_layer * layer_count * M * dp / iter_s / (double)devices / 1e12;
     out->mean_peak_tflops = peak_sum / (double)devices;
     out->mfu = out->tflops_per_device / out->mean_peak_tflops;                                                  // Eq. (2)
+    out->search_truncated = 0;
+    out->reserved_ = 0;
     return HH_OK;
 }
 
@@ -196,6 +198,7 @@ extern "C" int hh_plan_layers(const hh_sim_stage* stages, int n_stages, int tota
     hh_sim_result best_res{};
     bool found = false;
     long evaluated = 0;
+    bool truncated = false;
     const long budget = 2000000;   // candidates costed before the search stops widening
     // depth-first over the per-stage counts (minimum end-to-end time, rule 2, decides between the leaves)
     struct Frame { int p; int next; long used; };
@@ -220,7 +223,7 @@ extern "C" int hh_plan_layers(const hh_sim_stage* stages, int n_stages, int tota
             for (int q = 0; q < P; q++)
                 if (stages[q].memory_bytes && peak[q] > stages[q].memory_bytes) fits = false;
             if (fits && (!found || r.iter_ms < best_res.iter_ms)) { best_res = r; best_layers = cur; found = true; }
-            if (evaluated >= budget) break;
+            if (evaluated >= budget) { truncated = true; break; }
             continue;
         }
         if (rest < lo_suf[p + 1] || rest > hi_suf[p + 1]) continue;
@@ -230,6 +233,7 @@ extern "C" int hh_plan_layers(const hh_sim_stage* stages, int n_stages, int tota
     if (!found) return fail(HH_ERR_UNSUPPORTED_SHAPE, "no layer split within the search range fits the stages' memory");
     for (int p = 0; p < P; p++) layers_out[p] = best_layers[p];
     *best = best_res;
+    best->search_truncated = truncated ? 1 : 0;
     return HH_OK;
 }
 
@@ -251,7 +255,7 @@ extern "C" int hh_plan_order(const hh_sim_stage* groups, const int32_t* counts, 
     std::vector<int32_t> layers((size_t)P), best_layers;
     std::vector<int> best_perm;
     hh_sim_result best_res{};
-    bool found = false;
+    bool found = false, any_truncated = false;
     int first_error = HH_OK;
     do {   // std::next_permutation walks the orders lexicographically, so the first of equal times is kept
         size_t at = 0;
@@ -268,6 +272,7 @@ extern "C" int hh_plan_order(const hh_sim_stage* groups, const int32_t* counts, 
                                       flop_per_layer, slack, layers.data(), &r);
         if (rc == HH_ERR_UNSUPPORTED_SHAPE) continue;   // this order does not fit in memory
         if (rc != HH_OK) { first_error = rc; break; }
+        any_truncated = any_truncated || r.search_truncated;
         if (!found || r.iter_ms < best_res.iter_ms) { best_res = r; best_layers = layers; best_perm = perm; found = true; }
     } while (std::next_permutation(perm.begin(), perm.end()));
     if (first_error != HH_OK) return first_error;
@@ -275,5 +280,147 @@ extern "C" int hh_plan_order(const hh_sim_stage* groups, const int32_t* counts, 
     for (int k = 0; k < n_groups; k++) order_out[k] = best_perm[k];
     for (long q = 0; q < P; q++) layers_out[q] = best_layers[(size_t)q];
     *best = best_res;
+    best->search_truncated = any_truncated ? 1 : 0;   // some order's split search stopped at its budget
+    return HH_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The whole search tree of the automatic parallel planner (Section 3.3): data-parallel degree (level 2), one
+// tensor-parallel degree per accelerator type (level 3), and under every such leaf the pipeline level (stage order
+// and layer split, hh_plan_order).
+namespace {
+
+struct ClusterSearch {
+    const hh_cluster_group* groups;
+    int n_groups;
+    double cross;
+    int total_layers, micro_batch, seq, hidden, slack;
+    double flop_per_layer;
+    int d, n_micro;                 // current data-parallel degree and micro-batches per replica
+    int tp_idx[8];                  // current tensor-parallel degree index per group
+    bool found = false;
+    int error = HH_OK;
+    hh_cluster_plan best{};
+    std::vector<int32_t> best_layers;
+    int costed = 0;
+    bool truncated = false;
+
+    void leaf() {
+        std::vector<hh_sim_stage> g((size_t)n_groups);
+        std::vector<int32_t> counts((size_t)n_groups);
+        long P = 0;
+        for (int i = 0; i < n_groups; i++) {
+            const hh_cluster_group& c = groups[i];
+            const int t = 1 << tp_idx[i];
+            const long devices = (long)c.n_nodes * c.devices_per_node;
+            if (devices % ((long)d * t)) return;           // every accelerator is used
+            counts[i] = (int32_t)(devices / ((long)d * t));
+            if (counts[i] < 1) return;
+            P += counts[i];
+            hh_sim_stage& s = g[i];
+            s.n_layers = 0;
+            s.n_devices = d * t;
+            s.fwd_ms = c.fwd_ms_tp[tp_idx[i]];
+            s.bwd_ms = c.bwd_ms_tp[tp_idx[i]];
+            s.peak_tflops = c.peak_tflops;
+            s.link_gbytes_per_s = c.link_gbytes_per_s;
+            s.weight_bytes = c.weight_bytes / (uint64_t)t;
+            s.grad_bytes = c.grad_bytes / (uint64_t)t;
+            s.optimizer_bytes = c.optimizer_bytes / (uint64_t)t;
+            s.saved_act_bytes = c.saved_act_bytes_tp[tp_idx[i]];
+            s.memory_bytes = c.memory_bytes;
+        }
+        if (P > total_layers || P > 4096) return;
+        std::vector<int32_t> order((size_t)n_groups), layers((size_t)P);
+        hh_sim_result r{};
+        const int rc = hh_plan_order(g.data(), counts.data(), n_groups, cross, total_layers, n_micro, micro_batch, seq, hidden, d,
+                                     flop_per_layer, slack, order.data(), layers.data(), &r);
+        if (rc == HH_ERR_UNSUPPORTED_SHAPE) return;   // nothing fits in memory under this leaf
+        if (rc != HH_OK) { error = rc; return; }
+        costed++;
+        truncated = truncated || r.search_truncated;
+        // gradient all-reduce between the d replicas of a stage (ring: 2 (d-1)/d of the stage's fp32 gradient shard)
+        double ar = 0.0;
+        size_t at = 0;
+        for (int k = 0; k < n_groups; k++) {
+            const int gi = order[k];
+            const hh_cluster_group& c = groups[gi];
+            const int t = 1 << tp_idx[gi];
+            for (int q = 0; q < counts[gi]; q++, at++) {
+                if (d > 1 && c.dp_gbytes_per_s > 0.0) {
+                    const double bytes = 2.0 * (d - 1) / d * ((double)c.grad_bytes / t) * layers[at];
+                    ar = std::max(ar, bytes / (c.dp_gbytes_per_s * 1e9) * 1e3);
+                }
+            }
+        }
+        const double iter = r.iter_ms + ar;
+        if (found && !(iter < best.sim.iter_ms)) return;
+        hh_cluster_plan p{};
+        p.data_parallel = d;
+        for (int i = 0; i < n_groups; i++) { p.tensor_parallel[i] = 1 << tp_idx[i]; p.stages[i] = counts[i]; p.order[i] = order[i]; }
+        p.n_stages = (int32_t)P;
+        p.n_micro = n_micro;
+        p.pipeline_ms = r.iter_ms;
+        p.grad_allreduce_ms = ar;
+        p.sim = r;
+        const double scale = r.iter_ms / iter;          // the same work in a longer iteration
+        p.sim.iter_ms = iter;
+        p.sim.bubble_fraction = 1.0 - (1.0 - r.bubble_fraction) * scale;
+        p.sim.tokens_per_s_per_device = r.tokens_per_s_per_device * scale;
+        p.sim.tflops_per_device = r.tflops_per_device * scale;
+        p.sim.mfu = r.mfu * scale;
+        best = p;
+        best_layers = layers;
+        found = true;
+    }
+
+    void descend(int gi) {
+        if (error != HH_OK) return;
+        if (gi == n_groups) { leaf(); return; }
+        for (int i = 0; i < 4; i++) {
+            const int t = 1 << i;
+            if (groups[gi].devices_per_node % t) continue;                       // tensor parallelism stays inside a node
+            if (!(groups[gi].fwd_ms_tp[i] > 0.0) || !(groups[gi].bwd_ms_tp[i] > 0.0)) continue;   // not profiled
+            tp_idx[gi] = i;
+            descend(gi + 1);
+        }
+    }
+};
+
+}  // namespace
+
+extern "C" int hh_plan_cluster(const hh_cluster_group* groups, int n_groups, double cross_link_gbytes_per_s, int total_layers,
+                               int global_batch, int micro_batch, int seq, int hidden, double flop_per_layer, int slack,
+                               hh_cluster_plan* plan, int32_t* layers_out, int max_stages) {
+    if (!groups || !plan || !layers_out) return fail(HH_ERR_INVALID_ARG, "groups / plan / layers_out is NULL");
+    if (n_groups <= 0 || n_groups > 8) return fail(HH_ERR_INVALID_ARG, "n_groups must be in 1..8");
+    if (total_layers <= 0 || global_batch <= 0 || micro_batch <= 0 || seq <= 0 || hidden <= 0)
+        return fail(HH_ERR_INVALID_ARG, "total_layers, global_batch, micro_batch, seq and hidden must be positive");
+    if (!(flop_per_layer >= 0.0)) return fail(HH_ERR_INVALID_ARG, "flop_per_layer must not be negative");
+    if (slack < 0) return fail(HH_ERR_INVALID_ARG, "slack must not be negative");
+    if (max_stages <= 0) return fail(HH_ERR_INVALID_ARG, "max_stages must be positive");
+    long max_devices = 0;
+    for (int g = 0; g < n_groups; g++) {
+        if (groups[g].n_nodes <= 0 || groups[g].devices_per_node <= 0) return fail(HH_ERR_INVALID_ARG, "every group needs nodes and devices");
+        if (!(groups[g].peak_tflops > 0.0)) return fail(HH_ERR_INVALID_ARG, "peak_tflops must be positive");
+        max_devices = std::max(max_devices, (long)groups[g].n_nodes * groups[g].devices_per_node);
+    }
+    ClusterSearch s{};
+    s.groups = groups; s.n_groups = n_groups; s.cross = cross_link_gbytes_per_s; s.total_layers = total_layers;
+    s.micro_batch = micro_batch; s.seq = seq; s.hidden = hidden; s.slack = slack; s.flop_per_layer = flop_per_layer;
+    for (int d = 1; d <= max_devices && s.error == HH_OK; d++) {      // level 2, then level 3 below it, depth first
+        if (global_batch % ((long)d * micro_batch)) continue;
+        s.d = d;
+        s.n_micro = global_batch / (d * micro_batch);
+        if (s.n_micro < 1) continue;
+        s.descend(0);
+    }
+    if (s.error != HH_OK) return s.error;
+    if (!s.found) return fail(HH_ERR_UNSUPPORTED_SHAPE, "no parallel strategy of the search tree is feasible for this cluster");
+    if (s.best.n_stages > max_stages) return fail(HH_ERR_INVALID_ARG, "layers_out is shorter than the best plan's pipeline");
+    s.best.strategies_costed = s.costed;
+    s.best.sim.search_truncated = s.truncated ? 1 : 0;
+    *plan = s.best;
+    for (int q = 0; q < s.best.n_stages; q++) layers_out[q] = s.best_layers[(size_t)q];
     return HH_OK;
 }

@@ -201,3 +201,124 @@ def test_stage_order_argument_checks():
         hh.hh_plan_order(g * 9, [1] * 9, 0.0, 12, 2, 1, 128, 256, 1, 1e9)
     with pytest.raises(hh.HHError):
         hh.hh_plan_order(g, [3], 0.0, 2, 2, 1, 128, 256, 1, 1e9)       # fewer layers than stages
+
+
+# ---- the whole search tree: data-parallel and tensor-parallel levels above the pipeline level --------------------
+
+def cluster_group(nodes, devs, tf, tb, link=0.0, dp=0.0, w=0, g=0, o=0, mem=0, saved=(0, 0, 0, 0), peak=1000.0):
+    tf, tb = list(tf) + [0.0] * (4 - len(tf)), list(tb) + [0.0] * (4 - len(tb))
+    return hh.hh_cluster_group(nodes, devs, (hh.C.c_double * 4)(*tf), (hh.C.c_double * 4)(*tb), (hh.C.c_uint64 * 4)(*saved), peak, link, dp,
+                               w, g, o, mem)
+
+
+def oracle_group(g, msg_bytes):
+    return dict(n_nodes=g.n_nodes, devices_per_node=g.devices_per_node, fwd_ms_tp=list(g.fwd_ms_tp), bwd_ms_tp=list(g.bwd_ms_tp),
+                saved_act_bytes_tp=list(g.saved_act_bytes_tp),
+                link_ms=msg_bytes / (g.link_gbytes_per_s * 1e9) * 1e3 if g.link_gbytes_per_s > 0 else 0.0,
+                dp_ms_per_byte=1.0 / (g.dp_gbytes_per_s * 1e9) * 1e3 if g.dp_gbytes_per_s > 0 else 0.0,
+                weight_bytes=g.weight_bytes, grad_bytes=g.grad_bytes, optimizer_bytes=g.optimizer_bytes, memory_bytes=g.memory_bytes)
+
+
+def test_cluster_plan_hand_worked_cases_through_the_library():
+    # the cases worked out by hand for the oracle (tests/test_predictor_pins.py): one node of two devices, 2 layers, 4 samples
+    B, S, H = 1, 16, 8                       # message size is irrelevant here: all links are free
+    def plan(dp_gbs, tp2=True, **kw):
+        g = cluster_group(1, 2, (1.0, 0.6 if tp2 else 0.0), (2.0, 1.2 if tp2 else 0.0), dp=dp_gbs, g=100, **kw)
+        return hh.hh_plan_cluster([g], 0.0, 2, 4, B, S, H, 1e9, slack=4)
+    # all-reduce 2*(1/2)*100*2 bytes = 200 bytes at x ms per byte: x ms per byte <-> 1e-6 / x GB/s
+    p, layers = plan(1e-6 / 0.0075)
+    assert (p.data_parallel, p.tensor_parallel[0], p.stages[0], layers, p.n_micro) == (2, 1, 1, [2], 2)
+    assert p.pipeline_ms == pytest.approx(12.0) and p.grad_allreduce_ms == pytest.approx(1.5) and p.sim.iter_ms == pytest.approx(13.5)
+    assert p.sim.n_devices == 2 and p.strategies_costed == 3
+    # Eq. (1) on the whole iteration: seq * global batch / (devices * time)
+    assert p.sim.tokens_per_s_per_device == pytest.approx(S * 4 / (2 * 13.5e-3))
+    p, layers = plan(1e-6 / 0.02)
+    assert (p.data_parallel, p.tensor_parallel[0], layers) == (1, 2, [2]) and p.sim.iter_ms == pytest.approx(14.4)
+    p, layers = plan(1e-6 / 0.02, tp2=False)
+    assert (p.data_parallel, p.tensor_parallel[0], layers) == (1, 1, [1, 1]) and p.sim.iter_ms == pytest.approx(15.0)
+
+
+def test_cluster_plan_matches_exhaustive_search_on_small_random_clusters():
+    rng = random.Random(77)
+    checked = 0
+    for _ in range(40):
+        ng = rng.randint(1, 2)
+        B, S, H = rng.choice([1, 2]), 128, 64
+        msg = O.p2p_bytes(B, S, H)
+        groups = []
+        for _ in range(ng):
+            devs = rng.choice([1, 2, 4])
+            tf1, tb1 = rng.uniform(0.5, 2.0), rng.uniform(1.0, 4.0)
+            eff = [1.0, rng.uniform(0.55, 0.7), rng.uniform(0.3, 0.45), 0.0]      # time at degree 2^i relative to degree 1
+            prof = [rng.random() < 0.8 or i == 0 for i in range(4)]
+            tf = [tf1 * e if p else 0.0 for e, p in zip(eff, prof)]
+            tb = [tb1 * e if p else 0.0 for e, p in zip(eff, prof)]
+            w = rng.randint(50, 150)
+            mem = rng.choice([0, 0, rng.randint(400, 2500)])
+            groups.append(cluster_group(rng.randint(1, 2), devs, tf, tb, link=rng.choice([0.0, 1e-4, 1e-3]),
+                                        dp=rng.choice([0.0, 1e-6, 1e-5]), w=w, g=2 * w, o=6 * w, mem=mem,
+                                        saved=tuple(rng.randint(5, 60) // (1 << i) for i in range(4))))
+        total = rng.randint(2, 6)
+        gb = rng.choice([2, 4, 8]) * B
+        cross = rng.choice([0.0, 1e-4, 5e-5])
+        want = O.plan_cluster([oracle_group(g, msg) for g in groups], msg / (cross * 1e9) * 1e3 if cross > 0 else 0.0, total, gb, B)
+        try:
+            p, layers = hh.hh_plan_cluster(groups, cross, total, gb, B, S, H, 1e9, slack=total)
+        except hh.HHError as e:
+            assert e.code == hh.HH_ERR_UNSUPPORTED_SHAPE and want is None
+            continue
+        assert want is not None
+        checked += 1
+        assert p.sim.iter_ms == pytest.approx(want["iter_ms"], rel=1e-9)
+        assert p.pipeline_ms == pytest.approx(want["pipeline_ms"], rel=1e-9) and p.grad_allreduce_ms == pytest.approx(want["allreduce_ms"], rel=1e-9, abs=1e-15)
+        assert (p.data_parallel, list(p.tensor_parallel)[:ng], list(p.stages)[:ng], p.n_micro) == (want["d"], want["tp"], want["stages"], want["n_micro"])
+        assert sum(layers) == total and len(layers) == p.n_stages == sum(want["stages"])
+        # every accelerator is used
+        assert sum(p.data_parallel * p.tensor_parallel[i] * p.stages[i] for i in range(ng)) == sum(g.n_nodes * g.devices_per_node for g in groups) == p.sim.n_devices
+    assert checked >= 25
+
+
+def test_cluster_plan_for_a_two_speed_cluster_gives_the_slow_type_fewer_layers():
+    # a mix in the spirit of Section 4.3, scaled down: one node of 4 of a fast type and two nodes of 4 of a type 1.6x
+    # slower, 24 layers, 32 samples per iteration
+    fast = cluster_group(1, 4, (1.0, 0.62, 0.40), (2.0, 1.24, 0.80), link=25.0, dp=20.0, w=10**9, g=2 * 10**9, o=6 * 10**9)
+    slow = cluster_group(2, 4, (1.6, 1.0, 0.66), (3.2, 2.0, 1.3), link=25.0, dp=20.0, w=10**9, g=2 * 10**9, o=6 * 10**9)
+    p, layers = hh.hh_plan_cluster([fast, slow], 2.5, 24, 32, 1, 4096, 8192, 1.7e12, slack=0)
+    assert sum(layers) == 24 and p.n_stages == len(layers) and p.sim.search_truncated == 0
+    by_type = {0: [], 1: []}
+    pos = 0
+    for k in range(2):
+        g = p.order[k]
+        by_type[g] += layers[pos:pos + p.stages[g]]
+        pos += p.stages[g]
+    # load balance: a stage of the fast type carries more work per unit of its speed-adjusted time, i.e. at least as many
+    # layers per accelerator-second as a stage of the slow type
+    per_dev_fast = max(by_type[0]) / p.tensor_parallel[0]
+    per_dev_slow = min(by_type[1]) / p.tensor_parallel[1]
+    assert per_dev_fast >= per_dev_slow
+    assert p.data_parallel * p.tensor_parallel[0] * p.stages[0] == 4 and p.data_parallel * p.tensor_parallel[1] * p.stages[1] == 8
+    assert p.n_micro * p.data_parallel == 32
+
+
+def test_layer_split_reports_a_truncated_search():
+    # 14 stages with 5 candidate counts each: more leaves than the budget of costed candidates
+    st = [stage(0, 1.0 + 0.01 * i, 2.0) for i in range(14)]
+    layers, res = hh.hh_plan_layers(st, 70, 2, 1, 128, 64, 1, 1e9, slack=2)
+    assert res.search_truncated == 1 and sum(layers) == 70
+    layers, res = hh.hh_plan_layers(st[:4], 20, 2, 1, 128, 64, 1, 1e9, slack=2)
+    assert res.search_truncated == 0 and sum(layers) == 20
+
+
+def test_cluster_plan_argument_checks():
+    g = cluster_group(1, 2, (1.0,), (2.0,))
+    for args in [dict(n=0), dict(total=0), dict(gb=0), dict(mb=0), dict(slack=-1), dict(max_stages=0)]:
+        with pytest.raises(hh.HHError) as e:
+            hh.hh_plan_cluster([g] * args.get("n", 1), 0.0, args.get("total", 4), args.get("gb", 4), args.get("mb", 1), 128, 64, 1e9,
+                               slack=args.get("slack", 2), max_stages=args.get("max_stages", 64))
+        assert e.value.code == hh.HH_ERR_INVALID_ARG
+    with pytest.raises(hh.HHError) as e:                 # 3 samples in micro-batches of 2: no data-parallel degree fits
+        hh.hh_plan_cluster([g], 0.0, 4, 3, 2, 128, 64, 1e9)
+    assert e.value.code == hh.HH_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(hh.HHError) as e:                 # the best plan has 2 stages, the caller's array holds 1
+        hh.hh_plan_cluster([g], 0.0, 4, 1, 1, 128, 64, 1e9, max_stages=1)    # one sample: no replicas, only degree 1 profiled
+    assert e.value.code == hh.HH_ERR_INVALID_ARG

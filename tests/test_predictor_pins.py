@@ -242,3 +242,78 @@ def test_memory_rule_of_the_exhaustive_planner():
     g = [_group(1.0, 2.0, 0.0, mem=25, saved=10)]      # stage 0: one layer (20), stage 1: at most 2 -> 4 layers do not fit
     assert P.best_order_and_split(g, [2], 0.0, 4, 4) is None
     assert P.best_order_and_split(g, [2], 0.0, 3, 4)[1] == [1, 2]
+
+
+# ---- the whole search tree (Section 3.3: pipeline, data-parallel and tensor-parallel levels) ---------------------
+
+def _cluster_group(nodes, devs, tf, tb, link=0.0, dp=0.0, w=0, g=0, o=0, mem=0, saved=(0, 0, 0, 0)):
+    tf, tb = list(tf) + [0.0] * (4 - len(tf)), list(tb) + [0.0] * (4 - len(tb))
+    return dict(n_nodes=nodes, devices_per_node=devs, fwd_ms_tp=tf, bwd_ms_tp=tb, saved_act_bytes_tp=list(saved), link_ms=link,
+                dp_ms_per_byte=dp, weight_bytes=w, grad_bytes=g, optimizer_bytes=o, memory_bytes=mem)
+
+
+def test_cluster_plan_one_node_of_two_devices_hand_worked():
+    # 2 layers, 4 samples per iteration in micro-batches of 1.  A layer takes 1 + 2 (forward + backward) on a whole
+    # device and 0.6 + 1.2 on half of a tensor-parallel pair; fp32 gradient of a layer: 100 bytes.
+    #   d=1, t=1: 2 stages of 1 layer, 4 micro-batches: (4 + 2 - 1) * 3            = 15
+    #   d=1, t=2: 1 stage of 2 layers, 4 micro-batches: 4 * 2 * 1.8               = 14.4
+    #   d=2, t=1: 1 stage of 2 layers, 2 micro-batches: 2 * 2 * 3 = 12, plus the all-reduce 2*(1/2)*100*2 * x = 200 x
+    #   d=2, t=2 and d=4 would need 4 devices
+    def plan(x, tp2=True, g=100, **kw):
+        grp = _cluster_group(1, 2, (1.0, 0.6 if tp2 else 0.0), (2.0, 1.2 if tp2 else 0.0), dp=x, g=g, **kw)
+        return P.plan_cluster([grp], 0.0, 2, 4, 1)
+    r = plan(0.0075)
+    assert (r["d"], r["tp"], r["stages"], r["layers"], r["n_micro"]) == (2, [1], [1], [2], 2)
+    assert r["pipeline_ms"] == pytest.approx(12.0) and r["allreduce_ms"] == pytest.approx(1.5) and r["iter_ms"] == pytest.approx(13.5)
+    r = plan(0.02)                      # replicas would cost 12 + 4 = 16: the tensor-parallel pair wins
+    assert (r["d"], r["tp"], r["stages"], r["layers"], r["n_micro"]) == (1, [2], [1], [2], 4) and r["iter_ms"] == pytest.approx(14.4)
+    r = plan(0.02, tp2=False)           # degree 2 not profiled: the two-stage pipeline is left
+    assert (r["d"], r["tp"], r["stages"], r["layers"]) == (1, [1], [2], [1, 1]) and r["iter_ms"] == pytest.approx(15.0)
+    r = plan(0.012)                     # 12 + 2.4 = 14.4 ties with the pair: the first found (d = 1) is kept
+    assert (r["d"], r["tp"]) == (1, [2])
+    # memory: weights 10 + gradients 20 + optimizer 60 per layer and device share; capacity 100
+    #   d=2,t=1: 2 layers * 90 = 180 does not fit; d=1,t=2: 2 * 45 = 90 fits (14.4); d=1,t=1: 90 per stage fits (15)
+    r = plan(0.0, w=10, g=20, o=60, mem=100)
+    assert (r["d"], r["tp"]) == (1, [2]) and r["iter_ms"] == pytest.approx(14.4)
+    # saved activations of the live micro-batches count too: 6 bytes per layer at t=2 -> 90 + 1 live * 2 layers * 6 = 102
+    r = plan(0.0, w=10, g=20, o=60, mem=100, saved=(0, 6, 0, 0))
+    assert (r["d"], r["tp"], r["stages"]) == (1, [1], [2])
+    assert plan(0.0, w=10, g=20, o=60, mem=80) is None
+
+
+def test_cluster_plan_two_types_uses_every_device_and_orders_the_types():
+    # type 0: one device (1 + 2 per layer); type 1: a node of two devices (2 + 4 per layer each, 1.2 + 2.4 as a pair), link i
+    # between its stages; cross link c; 3 layers, 2 samples, micro-batch 1 -> d = 1 only (type 0 has a single device).
+    #   t1 = 1: stages (1, 2), the case worked out above: slow type first, 19 + 2c + 2i
+    #   t1 = 2: stages (1, 1): 3 layers over 2 stages, 2 micro-batches; with stage times (f0,b0), (f1,b1) and f1+b1 >= f0 the
+    #     1F1B iteration is f0 + c + 2 f1 + 2 b1, then stage 0's backwards: B0 ends at max(2 f0, f0+2c+f1+b1) + b0 and B1 at
+    #     max(that, f0 + 2c + 2 f1 + 2 b1) + b0.  Order (0,1), layers (2,1): f0=2,b0=4,f1=1.2,b1=2.4: B0: max(4, 5.6+2c)+4,
+    #     B1: max(9.6+2c, 9.2+2c)+4 = 13.6+2c.  Layers (1,2): f0=1,b0=2,f1=2.4,b1=4.8: B1 = max(.., 1+2c+14.4)+2 = 17.4+2c.
+    #     Order (1,0), layers (1,2) [type 1 first with 1 layer: f0=1.2,b0=2.4; type 0 second with 2: f1=2,b1=4]:
+    #     B0 = max(2.4, 1.2+2c+6)+2.4 = 9.6+2c, B1 = max(9.6+2c, 1.2+2c+12)+2.4 = 15.6+2c.  Layers (2,1): f0=2.4,b0=4.8,f1=1,b1=2:
+    #     B0 = max(4.8, 2.4+2c+3)+4.8 = 10.2+2c, B1 = max(10.2+2c, 2.4+2c+6)+4.8 = 15+2c.          => best 13.6 + 2c
+    c, i = 0.75, 0.125
+    groups = [_cluster_group(1, 1, (1.0,), (2.0,), link=9.0), _cluster_group(1, 2, (2.0, 1.2), (4.0, 2.4), link=i)]
+    for tf, tb, ln, want in [([2.0, 1.2], [4.0, 2.4], [c], 13.6 + 2 * c), ([1.0, 2.4], [2.0, 4.8], [c], 17.4 + 2 * c),
+                             ([1.2, 2.0], [2.4, 4.0], [c], 15.6 + 2 * c), ([2.4, 1.0], [4.8, 2.0], [c], 15.0 + 2 * c)]:
+        assert P.simulate(tf, tb, ln, 2)[0] == pytest.approx(want)
+    r = P.plan_cluster(groups, c, 3, 2, 1)
+    assert (r["d"], r["tp"], r["stages"], r["order"], r["layers"]) == (1, [1, 2], [1, 1], [0, 1], [2, 1])
+    assert r["iter_ms"] == pytest.approx(13.6 + 2 * c)
+    groups[1]["fwd_ms_tp"][1] = 0.0      # without the pair's profile only t1 = 1 is left
+    r = P.plan_cluster(groups, c, 3, 2, 1)
+    assert (r["tp"], r["stages"], r["order"], r["layers"]) == ([1, 1], [1, 2], [1, 0], [1, 1, 1])
+    assert r["iter_ms"] == pytest.approx(19 + 2 * c + 2 * i)
+
+
+def test_cluster_plan_data_parallel_degree_must_divide_batch_and_devices():
+    g = _cluster_group(2, 2, (1.0, 0.6, 0.0, 0.0), (2.0, 1.2, 0.0, 0.0))
+    # 4 devices, 6 samples, micro-batch 1: d in {1, 2, 3, 6} divides the batch, d*t in {1, 2, 4} the devices -> d in {1, 2}
+    seen = set()
+    for layers in (4, 8):
+        r = P.plan_cluster([g], 0.0, layers, 6, 1)
+        assert r["d"] in (1, 2) and r["d"] * r["tp"][0] * r["stages"][0] == 4 and r["n_micro"] * r["d"] == 6
+        assert sum(r["layers"]) == layers and len(r["layers"]) == r["stages"][0]
+        seen.add((r["d"], r["tp"][0]))
+    # micro-batch 4 does not divide 6 samples for any d: nothing to search
+    assert P.plan_cluster([g], 0.0, 4, 6, 4) is None
