@@ -20,10 +20,31 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
-# HBM-side bytes per GEMM call of the weight-gradient family at the default workload, from rocprofv3 FETCH_SIZE and
-# WRITE_SIZE passes over this command, scaled by a 1 GiB copy (x2.000 and x1.000): 1.029 GB fetched + 0.256 GB
-# written.  Holds for the kernel build those passes ran on; None for anything else.
-TRAFFIC_BYTES_PER_LAUNCH = {("cfg3", "gemm_tn"): 1.275e9}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "cfg3_layer_hbm_traffic_counters.txt")
+KERNEL_SOURCES = ("gemm_bf16.hip", "common.h")      # what the roofline kernel is built from
+
+
+def kernel_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2405_16256_amd", "csrc", f), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload, family):
+    """HBM-side bytes per GEMM call of the roofline family, from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary kept
+    under profiles/ (its last lines state workload, family, bytes and the hash of the kernel sources the counters were
+    taken on).  None when there is no figure for this workload and family or the kernel has changed since."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("bench_roofline_traffic "):
+                kv = dict(t.split("=", 1) for t in line.split()[1:])
+                if kv.get("workload") == workload and kv.get("family") == family and kv.get("kernel_sources_sha256") == kernel_sources_sha256():
+                    return float(kv["bytes_per_launch"])
+    except OSError:
+        pass
+    return None
 
 
 def workloads():
@@ -55,11 +76,14 @@ def workloads():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4-1f1b", "13b", "h8192-tp8", "h8192-gqa-tp8", "h8192-gqa"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-trace", action="store_true", help="do not time kernel families with events (no roofline object)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the two side figures of the default workload: the 4-layer x 8-micro-batch stage step against 32 "
+                         "single-layer passes, and the oracle timed on the tiny and the 7B-class configuration")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic) for scaling rocprofv3 byte counters")
     a = ap.parse_args()
@@ -129,12 +153,19 @@ def main():
         gemms = {n: v for n, v in fam_all.items() if n.startswith("gemm") and v[0] > 0}
         dom = max(gemms, key=lambda n: gemms[n][1]) if gemms else "gemm_tn"
         hh.hh_trace_begin(ctx, a.steps * k * M * 8, [dom])
+    # one event per step boundary on the stream the library launches on (torch's current stream): per-step
+    # durations for the median; the mean comes from the host clock around the whole region
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    marks[0].record()
+    for i in range(a.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     fam = hh.hh_trace_end(ctx) if not a.no_trace else {}
+    per_step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
+    median_ms = per_step_ms[len(per_step_ms) // 2] if len(per_step_ms) % 2 else 0.5 * (per_step_ms[len(per_step_ms) // 2 - 1] + per_step_ms[len(per_step_ms) // 2])
 
     f, b = hh.hh_layer_flops(cfg)
     flop_step = (f + b) * k * M
@@ -151,8 +182,9 @@ def main():
         achieved = dwork / (dms * 1e-3) / 1e12
         roofline = {"kernel": "k_gemm_dma (%s; one launch = one GEMM call incl. its k-split tail)" % dom, "bound": "mfma",
                     "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((a.workload, dom)),
-                    "traffic_unit": "bytes per launch", "launches": launches,
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(a.workload, dom),
+                    "traffic_unit": "bytes per launch", "traffic_source": "profiles/" + os.path.basename(TRAFFIC_PROFILE) + " (null: no counter pass on this kernel build)",
+                    "launches": launches,
                     "avg_launch_ms": round(dms / launches, 4), "flop_per_launch": dwork / launches,
                     "ms_per_step": round(dms / a.steps, 4)}
 
@@ -186,8 +218,69 @@ def main():
         # the run also serves as an end-to-end parity check of the timed configuration
         err = L.rel_err(L.to_np(ys[0]), yo) if k == 1 else None
         out["parity_y_rel_fro"] = None if err is None else float("%.3e" % err)
+    if a.workload == "cfg3" and not a.no_extras:
+        out["stage_step_cfg4"] = stage_step_ratio(hh, I, L, ctx, median_ms)
+        if not a.no_cpu_baseline:
+            out["cpu_baseline_other_configs"] = oracle_times(I)
     print(json.dumps(out), flush=True)
     hh.hh_ctx_destroy(ctx)
+
+
+def stage_step_ratio(hh, I, L, ctx, layer_ms):
+    """The pipeline-stage workload (4 layers x 8 micro-batches of the default layer shape) in one hh_stage_step call,
+    against 32 times the single-layer step measured just before: what the stage scheduler adds."""
+    import torch
+    wl = workloads()["cfg4"]
+    s, k, M, seed = wl["shape"], wl["k"], wl["M"], wl["seed"]
+    cfg = L.cfg_of(s, True)
+    layers = [L.DeviceLayer(I.layer_weights(seed, l, s, True), s, True) for l in range(k)]
+    acts = [I.activations(seed, s, m, True) for m in range(2)]
+    xs = [L.to_dev(acts[m % 2][0], True) for m in range(M)]
+    dys = [L.to_dev(acts[m % 2][1], True) for m in range(M)]
+    ys = [torch.empty_like(t) for t in xs]
+    dxs = [torch.empty_like(t) for t in xs]
+    pool_b, ws_b = hh.hh_stage_sizes(cfg, k, M)
+    pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
+    wsp = torch.empty(ws_b, dtype=torch.uint8, device=L.DEV)
+    wst, gst = [l.wstruct for l in layers], [l.gstruct for l in layers]
+    st = L.stream_ptr()
+    times = []
+    for i in range(5):                          # first one untimed
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
+        a1.record()
+        torch.cuda.synchronize()
+        if i:
+            times.append(a0.elapsed_time(a1))
+    times.sort()
+    ms = 0.5 * (times[1] + times[2])
+    f, b = hh.hh_layer_flops(cfg)
+    return {"workload": wl["name"], "ms_per_step_median_of_4": round(ms, 3), "tflops": round((f + b) * k * M / (ms * 1e-3) / 1e12, 1),
+            "tokens_per_s": round(s.tokens * M / (ms * 1e-3), 1), "single_layer_ms_median": round(layer_ms, 4),
+            "step_over_32_layer_passes": round(ms / (k * M * layer_ms), 4)}
+
+
+def oracle_times(I):
+    """The oracle, as it stands, on one layer forward+backward of the tiny fp32 configuration (median of 5) and of the
+    7B-class configuration (one run): the reported CPU baseline of the other layer configurations."""
+    from oracle import decoder_oracle as O
+    res = {}
+    for name, s, bf16, reps in (("cfg1", I.CFG1, False, 5), ("cfg2", I.CFG2, True, 1)):
+        w = I.layer_weights(I.SEEDS[name], 0, s, bf16)
+        x, dy = I.activations(I.SEEDS[name], s, 0, bf16)
+        ts = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            _, cache = O.layer_forward(x, w, s.n_heads, s.head_dim, s.rms_eps, s.rope_base, s.kv_heads)
+            O.layer_backward(dy, w, cache)
+            ts.append(time.perf_counter() - t0)
+        ts.sort()
+        t = ts[len(ts) // 2]
+        flop = 3.0 * (s.tokens * (2.0 * (s.attn + 2 * s.attn_kv + s.attn) * s.hidden + 6.0 * s.hidden * s.ffn) +
+                      4.0 * s.head_dim * s.micro_batch * s.n_heads * (s.seq * (s.seq + 1) / 2))
+        res[name] = {"seconds": round(t, 4), "tflops_fp64": round(flop / t / 1e12, 4), "runs": reps}
+    return res
 
 
 if __name__ == "__main__":

@@ -43,6 +43,9 @@
  *    below 2^31 bytes, every (packed) weight below 2^32 - 2^25 bytes
  *    (HH_ERR_UNSUPPORTED_SHAPE otherwise).
  *  - Argument validation happens before any GPU work is enqueued.
+ *  - A context is used by one host thread at a time (the hot calls keep per-call state in it); use one context
+ *    per thread.  A rotary table that a later call replaces by a longer one stays alive until hh_ctx_destroy,
+ *    so work enqueued or captured earlier keeps reading valid memory.
  */
 #ifndef HH_H
 #define HH_H
@@ -121,10 +124,11 @@ typedef struct hh_ctx hh_ctx;      /* opaque: device id, rotary table */
 const char *hh_last_error(void);
 
 /* Create / destroy a context on HIP device `device`.  HH_ERR_DEVICE when there
- * is no such GPU.  Destroy frees the rotary table; it does not synchronise. */
+ * is no such GPU.  Destroy frees the rotary tables; it does not synchronise: the
+ * caller makes sure the work it enqueued with the context has finished. */
 int hh_ctx_create(hh_ctx **out, int device);
 int hh_ctx_destroy(hh_ctx *ctx);
-/* Build the rotary table for cfg now (allocates, copies, synchronises). */
+/* Build the rotary table for cfg now (allocates and copies; a blocking host-to-device copy). */
 int hh_ctx_reserve(hh_ctx *ctx, const hh_layer_cfg *cfg);
 
 /* Model flops of one layer on one micro-batch (host arithmetic only). */

@@ -548,11 +548,25 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float* __restrict__
     }
 }
 
-constexpr int NUM_CU = 256;
+// Compute units of the current device (one persistent workgroup each), asked once per device.
+static int device_cus(hipError_t& err) {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    err = hipGetDevice(&dev);
+    if (err != hipSuccess) return 0;
+    const int slot = dev & 63;
+    int n = cached[slot].load(std::memory_order_relaxed);
+    if (n > 0) return n;
+    err = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (err != hipSuccess) return 0;
+    if (n < 8) n = 8;
+    cached[slot].store(n, std::memory_order_relaxed);
+    return n;
+}
 
-// Full rounds of 256 tiles run one tile per workgroup.  A last, partial round of R tiles would leave
-// most CUs idle, so it is cut along k into floor(256 / R) shares per tile (fp32 partials in `ws`,
-// summed in a fixed order by a small second kernel).
+// Full rounds of one tile per compute unit run as one persistent workgroup per unit.  A last, partial round of R
+// tiles would leave most units idle, so it is cut along k into floor(units / R) shares per tile (fp32 partials in
+// `ws`, summed in a fixed order by a small second kernel).
 template <int KIND, bool OUT_F32>
 static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
     constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES + 8 * 4096;   // two stages + the epilogue patches of the 8 waves
@@ -560,6 +574,9 @@ static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_byt
     auto kern = k_gemm_dma<KIND, OUT_F32>;
     const hipError_t e = allow_lds((const void*)kern, LDS, lds_ok);
     if (e != hipSuccess) return e;
+    hipError_t ce = hipSuccess;
+    const int NUM_CU = device_cus(ce);
+    if (ce != hipSuccess) return ce;
     const int tiles = ((g.M + DTILE - 1) / DTILE) * ((g.N + DTILE - 1) / DTILE);
     const int nk = (g.K + DK - 1) / DK;
     int full = tiles, tail = 0, ksplit = 1;

@@ -86,6 +86,7 @@ struct hh_ctx {
     bool trace_on;
     uint32_t trace_mask;          // families recorded while trace_on
     void* gemm_ws;                // k-split scratch inside the caller's workspace, set by each hot call
+    std::vector<float*> retired_tables;   // rotary tables replaced by a larger one: freed with the context
 };
 
 extern "C" int hh_ctx_create(hh_ctx** out, int device) {
@@ -104,7 +105,7 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
     e = static_scratch_init(device);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
-    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false, 0u, nullptr};
+    hh_ctx* c = new (std::nothrow) hh_ctx{device, nullptr, 0, 0, 0.f, {}, 0, false, 0u, nullptr, {}};
     if (!c) return fail(HH_ERR_INVALID_ARG, "hh_ctx_create: out of host memory");
     *out = c;
     return HH_OK;
@@ -113,6 +114,7 @@ extern "C" int hh_ctx_create(hh_ctx** out, int device) {
 extern "C" int hh_ctx_destroy(hh_ctx* ctx) {
     if (!ctx) return HH_OK;
     if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+    for (float* t : ctx->retired_tables) (void)hipFree(t);
     for (auto& r : ctx->trace) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete ctx;
     return HH_OK;
@@ -279,8 +281,9 @@ static int ensure_rope(hh_ctx* ctx, const hh_layer_cfg* c) {
     if (ctx->rope_table && ctx->rope_seq >= c->seq && ctx->rope_dim == c->head_dim && ctx->rope_base == c->rope_base) return HH_OK;
     HIP_TRY(hipSetDevice(ctx->device));
     if (ctx->rope_table) {
-        HIP_TRY(hipDeviceSynchronize());  // earlier launches may still read the old table
-        HIP_TRY(hipFree(ctx->rope_table));
+        // launches already enqueued, and graphs recorded earlier, still read the old table: it stays alive
+        // until the context is destroyed
+        ctx->retired_tables.push_back(ctx->rope_table);
         ctx->rope_table = nullptr;
     }
     const int S = c->seq, half = c->head_dim / 2;

@@ -4,8 +4,8 @@ fed with the measured computation time of a layer on each accelerator type).
 For the 7B-class and the 140B-class TP-share layer shapes, at seq {1024, 2048, 4096} x micro-batch
 {1, 2, 4} and a stage depth of 1..12 layers, runs hh_layer_profile and prints one JSON line per
 (shape, seq, micro-batch, depth) with the per-layer forward / backward milliseconds and TFLOP/s and the
-byte figures of the profile record.  Layers of a stage share one set of seeded weights (timing does not
-depend on the values), so the deepest stage needs one layer's parameters only.
+byte figures of the profile record.  Every layer of a stage has its own seeded weights and its own fp32
+gradient buffers, as in a real stage (12 layers of the 140B-class share hold 16 GB of them).
 
   python -m paper_2405_16256_amd.profile_sweep [--depths 1,4,12] [--iters 3] [--quick]
 """
@@ -35,9 +35,7 @@ def main() -> None:
     ctx = hh.hh_ctx_create(0)
     seed = I.SEEDS["cfg5"]
     for name, base in (("7B-class", I.CFG2), ("140B-class TP=8 share", I.CFG3)):
-        w = I.layer_weights(seed, 0, base, True)
-        layer = L.DeviceLayer(w, base, True)
-        del w
+        layers = [L.DeviceLayer(I.layer_weights(seed, l, base, True), base, True) for l in range(max(depths))]
         for S in seqs:
             for B in mbs:
                 s = I.LayerShape(base.hidden, base.n_heads, base.head_dim, base.ffn, S, B)
@@ -48,7 +46,7 @@ def main() -> None:
                     pool_b, ws_b = hh.hh_stage_sizes(cfg, k, 1)
                     pool = torch.empty(pool_b, dtype=torch.uint8, device=L.DEV)
                     wsp = torch.empty(ws_b, dtype=torch.uint8, device=L.DEV)
-                    recs = hh.hh_layer_profile(ctx, cfg, [layer.wstruct] * k, [layer.gstruct] * k, x, dy, a.warmup,
+                    recs = hh.hh_layer_profile(ctx, cfg, [l.wstruct for l in layers[:k]], [l.gstruct for l in layers[:k]], x, dy, a.warmup,
                                                a.iters, pool, wsp, L.stream_ptr())
                     f = [r.fwd_ms for r in recs]
                     b = [r.bwd_ms for r in recs]
@@ -64,7 +62,7 @@ def main() -> None:
                         "workspace_bytes": r0.workspace_bytes}), flush=True)
                     del pool, wsp
                 del x, dy
-        del layer
+        del layers
         torch.cuda.empty_cache()
     hh.hh_ctx_destroy(ctx)
 
