@@ -190,7 +190,8 @@ def main():
 
     out = {
         "metric": "decoder-layer fwd+bwd TFLOP/s on 1 GPU", "value": round(tflops, 2), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4), "ms_per_step_median": round(median_ms, 4),
+        "ms_per_step_min_max": [round(per_step_ms[0], 4), round(per_step_ms[-1], 4)],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl["name"], "layers": k, "micro_batches": M, "live_micro_batches": live, "activation_pool_bytes": pool_b, "tokens_per_micro_batch": s.tokens,
                    "model_flop_per_step": flop_step},
