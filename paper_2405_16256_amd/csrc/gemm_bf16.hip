@@ -294,11 +294,11 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
                                                   const bf16_t* __restrict__ B, int ldb, uint32_t b_bytes,
                                                   void* __restrict__ Cv, int ldc, const bf16_t* R, int ldr,
                                                   int M, int N, int K, int accumulate,
-                                                  int block0, int block_end, int ksplit, float* __restrict__ partial) {
-    // ksplit == 1: the workgroup walks tiles block0 + blockIdx.x, + gridDim.x, ... < block_end over the whole
-    //   k range; the first DMA stages of the next tile are issued before the epilogue of the current one.
-    // ksplit  > 1: workgroup blockIdx.x computes tile (block0 + blockIdx.x / ksplit) over the
-    //   (blockIdx.x % ksplit)-th share of the k range and writes fp32 sums to partial[blockIdx.x][256][256].
+                                                  int full, int n_items, int ksplit, float* __restrict__ partial) {
+    // The workgroup walks work items blockIdx.x, + gridDim.x, ... < n_items.  Items below `full` are whole tiles
+    // (all of k, written out through the epilogue).  Item full + q is the (q % ksplit)-th share of the k range of
+    // tile full + q / ksplit; its fp32 sums go to partial[q][256][256] and k_splitk_reduce finishes those tiles.
+    // The first DMA stages of the next item are issued before the current one is written out.
     constexpr bool A_KC = (KIND != GEMM_TN);
     constexpr bool B_KC = (KIND == GEMM_NT);
     using DA = DmaTile<A_KC>;
@@ -307,14 +307,23 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
     extern __shared__ __attribute__((aligned(1024))) char smem[];   // [stage][A 32 KB | B 32 KB]
 
     const int tiles_m = (M + DTILE - 1) / DTILE, tiles_n = (N + DTILE - 1) / DTILE;
-    const int chunk = ksplit > 1 ? (int)blockIdx.x % ksplit : 0;
-    const int stride = ksplit > 1 ? block_end : (int)gridDim.x;        // split workgroups own a single tile
-    int tix = block0 + (ksplit > 1 ? (int)blockIdx.x / ksplit : (int)blockIdx.x);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
     const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
     const int nk_all = (K + DK - 1) / DK;
-    const int kbeg = (int)((long)chunk * nk_all / ksplit), kend = (int)((long)(chunk + 1) * nk_all / ksplit);
-    const int nk = kend - kbeg;
+    // work item -> tile index, first k tile, number of k tiles, slot in `partial` (-1: whole tile)
+    int tix, kbeg, nk, slot;
+    auto decode = [&](int item) {
+        if (item < full) { tix = item; kbeg = 0; nk = nk_all; slot = -1; }
+        else {
+            const int q = item - full, chunk = q % ksplit;
+            tix = full + q / ksplit;
+            kbeg = (int)((long)chunk * nk_all / ksplit);
+            nk = (int)((long)(chunk + 1) * nk_all / ksplit) - kbeg;
+            slot = q;
+        }
+    };
+    int item = (int)blockIdx.x;
+    decode(item);
 
     const uint64_t pa = (uint64_t)A, pb = (uint64_t)B;
     const i32x4 rsA = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)a_bytes, 0x00020000};
@@ -423,8 +432,21 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
             }
         }
 
-        if (ksplit > 1) {
-            float* pt = partial + (size_t)blockIdx.x * (DTILE * DTILE);
+        // next piece of work of this workgroup: start its loads before writing this one out
+        const int cm0 = m0, cn0 = n0, cacc = accumulate, cslot = slot;
+        item += (int)gridDim.x;
+        const bool has_next = item < n_items;
+        if (has_next) {
+            decode(item);
+            tile_of_index(tix, tiles_m, tiles_n, tm, tn);
+            m0 = tm * DTILE; n0 = tn * DTILE;
+            __syncthreads();   // every wave has finished reading the LDS stages
+            start_tile(m0, n0);
+            fresh = false;
+        }
+
+        if (cslot >= 0) {   // a share of the k range: raw fp32 sums, finished by the reduction kernel
+            float* pt = partial + (size_t)cslot * (DTILE * DTILE);
 #pragma unroll
             for (int i = 0; i < TM; i++)
 #pragma unroll
@@ -433,19 +455,8 @@ __global__ __launch_bounds__(512) void k_gemm_dma(const bf16_t* __restrict__ A, 
                     for (int g = 0; g < 4; g++)
                         *reinterpret_cast<float4*>(pt + (wm + 32 * i + (lane & 31)) * DTILE + wn + 32 * j + 8 * g + 4 * hf) =
                             make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            return;
-        }
-
-        // next piece of work of this workgroup: start its loads before writing this one out
-        const int cm0 = m0, cn0 = n0, cacc = accumulate;
-        tix += stride;
-        const bool has_next = tix < block_end;
-        if (has_next) {
-            tile_of_index(tix, tiles_m, tiles_n, tm, tn);
-            m0 = tm * DTILE; n0 = tn * DTILE;
-            __syncthreads();   // every wave has finished reading the LDS stages
-            start_tile(m0, n0);
-            fresh = false;
+            if (!has_next) return;
+            continue;
         }
 
         // Epilogue.  In the accumulators a lane owns one row and 4-column pieces of it, which would make every
@@ -565,8 +576,8 @@ static int device_cus(hipError_t& err) {
 }
 
 // Full rounds of one tile per compute unit run as one persistent workgroup per unit.  A last, partial round of R
-// tiles would leave most units idle, so it is cut along k into floor(units / R) shares per tile (fp32 partials in
-// `ws`, summed in a fixed order by a small second kernel).
+// tiles would leave most units idle, so it is cut along k into floor(units / R) shares per tile, which the same
+// workgroups take up after their whole tiles (fp32 partials in `ws`, summed in a fixed order by a small second kernel).
 template <int KIND, bool OUT_F32>
 static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_bytes, hipStream_t st) {
     constexpr int LDS = DSTAGES * 2 * DSTAGE_BYTES + 8 * 4096;   // two stages + the epilogue patches of the 8 waves
@@ -587,17 +598,14 @@ static hipError_t launch_dma(const GemmDesc& g, uint32_t a_bytes, uint32_t b_byt
         while (s > 1 && (nk / s < 4 || (size_t)rem * s * DTILE * DTILE * sizeof(float) > g.ws_bytes)) s--;
         if (s > 1) { full = tiles - rem; tail = rem; ksplit = s; }
     }
-    if (full > 0)   // one workgroup per CU walks its share of the tiles
-        kern<<<full < NUM_CU ? full : NUM_CU, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes,
-                                                               g.C, g.ldc, (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate,
-                                                               0, full, 1, nullptr);
-    if (tail > 0) {
-        kern<<<tail * ksplit, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes, g.C, g.ldc,
-                                              (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate, full, full + tail, ksplit,
-                                              (float*)g.ws);
+    // one launch: a persistent workgroup per CU walks the whole tiles and then the k shares of the tail tiles
+    const int n_items = full + tail * ksplit;
+    kern<<<n_items < NUM_CU ? n_items : NUM_CU, 512, LDS, st>>>((const bf16_t*)g.A, g.lda, a_bytes, (const bf16_t*)g.B, g.ldb, b_bytes,
+                                                                 g.C, g.ldc, (const bf16_t*)g.R, g.ldr, g.M, g.N, g.K, g.accumulate,
+                                                                 full, n_items, ksplit, (float*)g.ws);
+    if (tail > 0)
         k_splitk_reduce<OUT_F32><<<tail * 64, 256, 0, st>>>((const float*)g.ws, ksplit, full, g.C, g.ldc, (const bf16_t*)g.R,
                                                             g.ldr, g.M, g.N, g.accumulate);
-    }
     return hipGetLastError();
 }
 

@@ -730,3 +730,46 @@ def test_fp32_seeded_random_small_shapes(ctx):
         mb = int(rng.choice([1, 2, 3]))
         s = I.LayerShape(hidden, nh, d, ffn, seq, mb, n_kv_heads=nkv)
         check_layer(ctx, s, False, 400 + case, packed=bool(case % 2), label="random-f32-%d" % case)
+
+
+def test_a_recorded_graph_survives_a_later_longer_rotary_table(ctx):
+    # a graph recorded at one sequence length keeps the rotary table of that time; a later call with a longer sequence
+    # builds a new table and must leave the old one alive for the graph's replays
+    s = I.LayerShape(256, 2, 128, 320, 96, 1)
+    own = hh.hh_ctx_create(0)
+    try:
+        cfg = L.cfg_of(s, True)
+        layer = L.DeviceLayer(I.layer_weights(95, 0, s, True), s, True)
+        x = L.to_dev(I.activations(95, s, 0, True)[0], True)
+        y = torch.empty_like(x)
+        saved_b, ws_b = hh.hh_layer_sizes(cfg)
+        ws = torch.empty(saved_b + ws_b, dtype=torch.uint8, device=L.DEV)
+        hh.hh_ctx_reserve(own, cfg)
+        hh.hh_layer_fwd(own, cfg, layer.wstruct, x, y, None, ws, L.stream_ptr())
+        torch.cuda.synchronize()
+        want = y.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                hh.hh_layer_fwd(own, cfg, layer.wstruct, x, y, None, ws, L.stream_ptr())
+        torch.cuda.synchronize()
+        # a longer sequence on the same context: new table
+        s2 = I.LayerShape(256, 2, 128, 320, 700, 1)
+        cfg2 = L.cfg_of(s2, True)
+        x2 = L.to_dev(I.activations(96, s2, 0, True)[0], True)
+        y2 = torch.empty_like(x2)
+        sb2, wb2 = hh.hh_layer_sizes(cfg2)
+        ws2 = torch.empty(sb2 + wb2, dtype=torch.uint8, device=L.DEV)
+        hh.hh_layer_fwd(own, cfg2, layer.wstruct, x2, y2, None, ws2, L.stream_ptr())
+        torch.cuda.synchronize()
+        for _ in range(2):
+            y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, want)
+    finally:
+        torch.cuda.synchronize()
+        hh.hh_ctx_destroy(own)
