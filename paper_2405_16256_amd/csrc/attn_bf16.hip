@@ -15,7 +15,16 @@
 //
 // Backward is two deterministic passes (no atomics): a query-stationary pass
 // for dQ and a key-stationary pass for dK, dV, both recomputing P from the
-// saved log-sum-exp.  delta[s] = <dO[s], O[s]> is formed by the dQ pass and handed to the dK/dV pass.
+// saved log-sum-exp.  On large launches they are two kernels and the dQ pass forms
+// delta[s] = <dO[s], O[s]> for the dK/dV pass; on launches of few workgroups, where
+// each pass alone is bound by its longest job, a small kernel forms delta and one
+// launch deals out the jobs of both passes together.
+//
+// The loops are bound by instruction issue, not by the matrix pipes, so the vector
+// work per tile is kept to the softmax arithmetic itself: LDS addresses are per-lane
+// tables whose tile, row-block and k-step displacements sit in the instructions'
+// offset fields, the lane part of every tile-load address is computed once, and the
+// causal mask is applied by a branch on the (few) tiles that touch the diagonal.
 #include "common.h"
 #include "kernels.h"
 
@@ -43,57 +52,6 @@ struct Tile {
         if (D == 128) { const int x = row & 15; return ((x & 3) << 2) | (x >> 2); }
         const int x = (row >> 1) & 7;
         return ((x & 1) << 2) | (x >> 1);
-    }
-
-    // Issue this wave's share of the tile whose first row is token tok0 (rows of ld elements, column col0).
-    // Rows past the buffer extent deposit zeros.
-    template <int NW = ATHREADS / WAVE>
-    __device__ static __forceinline__ void dma(uint32_t lds_tile, i32x4 rs, uint32_t tok0, int ld, int col0) {
-        constexpr int PER_WAVE = BYTES / 1024 / NW;   // DMA instructions per wave
-        const int w = threadIdx.x >> 6, L = threadIdx.x & 63;
-#pragma unroll
-        for (int i = 0; i < PER_WAVE; i++) {
-            const int q = w * PER_WAVE + i;                 // 1 KB block of the tile
-            const int row = q * (1024 / ROWB) + L / CPR;
-            const int logical = (L % CPR) ^ swz(row);
-            const uint32_t voff = ((tok0 + row) * (uint32_t)ld + (uint32_t)(col0 + logical * 8)) * 2u;
-            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + q * 1024);
-            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(dst), "v"(voff), "s"(rs) : "memory");
-        }
-    }
-    // Per-lane byte offsets of the fragment reads, computed once per kernel: the swizzle depends only
-    // on the lane, so inside the loops every LDS address is (stage base + table entry + constant).
-    struct Offsets {
-        int rows[D / 16];        // frag_rows: k step kk, row block at 0
-        int cols0[D / 32];       // frag_cols: channel block dt, k step 0, first 4 rows
-        int cols1[D / 32];       //            ... rows +8
-    };
-    __device__ static __forceinline__ Offsets offsets() {
-        Offsets o;
-        const int l = threadIdx.x & 63;
-        const int r = l & 31;
-#pragma unroll
-        for (int kk = 0; kk < D / 16; kk++) o.rows[kk] = r * ROWB + (((2 * kk + (l >> 5)) ^ swz(r)) << 4);
-        const int row = 4 * (l >> 5) + ((l & 15) >> 2);
-#pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) {
-            const int col = 32 * dt + 16 * ((l >> 4) & 1) + 4 * (l & 3);
-            const int c = col >> 3, within = (col & 7) * 2;
-            o.cols0[dt] = row * ROWB + ((c ^ swz(row)) << 4) + within;
-            o.cols1[dt] = (row + 8) * ROWB + ((c ^ swz(row + 8)) << 4) + within;
-        }
-        return o;
-    }
-    // rows 32*rblk + (lane%32), k = 16kk + 8(lane/32) .. +7 along d
-    __device__ static __forceinline__ bf16x8 frag_rows(const char* t, const Offsets& o, int rblk, int kk) {
-        return *reinterpret_cast<const bf16x8*>(t + rblk * 32 * ROWB + o.rows[kk]);
-    }
-    // transposed fragment: result row = tile column 32*dt + (lane%32); the lane's 8 k values are tile
-    // rows 16kk + 8j + 4(lane/32) + e  (j = 0,1; e = 0..3)
-    __device__ static __forceinline__ bf16x8 frag_cols(const char* t, const Offsets& o, int dt, int kk) {
-        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(t + kk * 16 * ROWB + o.cols0[dt]));
-        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(t + kk * 16 * ROWB + o.cols1[dt]));
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
 };
 
@@ -145,43 +103,136 @@ __device__ __forceinline__ void load_qfrag(bf16x8 (&f)[D / 16], __amdgpu_buffer_
     }
 }
 
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+
+// LDS byte addresses of one lane's fragment reads of a staged tile; the tile's own address and the
+// row-block / k-step displacements are compile-time constants that go into the instructions' offset fields.
+template <int D>
+struct FragAddr {
+    uint32_t rows[D / 16], cols0[D / 32], cols1[D / 32];
+    // rows: fragment of tile rows (lane%32), 8 channels 16kk + 8(lane/32) .. of k step kk
+    // cols0/cols1: transposed fragment of channel block dt -- result row = tile column 32dt + (lane%32), the
+    //   lane's 8 k values are tile rows 8j + 4(lane/32) + e (j = 0,1: cols0, cols1; e = 0..3) of a k step
+    __device__ __forceinline__ void init(uint32_t base) {
+        using TL = Tile<D>;
+        const int l = threadIdx.x & 63;
+        const int r = l & 31;
+#pragma unroll
+        for (int k = 0; k < D / 16; k++) rows[k] = base + r * TL::ROWB + (((2 * k + (l >> 5)) ^ TL::swz(r)) << 4);
+        const int row = 4 * (l >> 5) + ((l & 15) >> 2);
+#pragma unroll
+        for (int t = 0; t < D / 32; t++) {
+            const int col = 32 * t + 16 * ((l >> 4) & 1) + 4 * (l & 3);
+            const int c = col >> 3, within = (col & 7) * 2;
+            cols0[t] = base + row * TL::ROWB + ((c ^ TL::swz(row)) << 4) + within;
+            cols1[t] = base + (row + 8) * TL::ROWB + ((c ^ TL::swz(row + 8)) << 4) + within;
+        }
+    }
+    // the tables follow the tile to another LDS address
+    __device__ __forceinline__ void shift(int by) {
+#pragma unroll
+        for (int k = 0; k < D / 16; k++) rows[k] += by;
+#pragma unroll
+        for (int t = 0; t < D / 32; t++) { cols0[t] += by; cols1[t] += by; }
+    }
+    __device__ __forceinline__ bf16x8 frag_rows(int disp, int rblk, int kk) const {
+        return *(const lds_bf16x8*)(size_t)(rows[kk] + (uint32_t)(disp + rblk * 32 * Tile<D>::ROWB));
+    }
+    __device__ __forceinline__ bf16x8 frag_cols(int disp, int dt, int kk) const {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(size_t)(cols0[dt] + (uint32_t)(disp + kk * 16 * Tile<D>::ROWB)));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(size_t)(cols1[dt] + (uint32_t)(disp + kk * 16 * Tile<D>::ROWB)));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+};
+
+// Direct global->LDS loads of a tile, NW waves sharing it: instruction i of wave w deposits the 1 KB block
+// w*PER_WAVE + i.  off[] is the lane part of its source byte offset (tile row and swizzled chunk, for rows of ld
+// elements), computed once; the tile's own offset (first token, column) is a scalar added per instruction.  The
+// whole offset goes through the buffer's range check, so rows past the buffer extent deposit zeros.
+template <int D, int NW>
+struct DmaLane {
+    static constexpr int PER_WAVE = Tile<D>::BYTES / 1024 / NW;
+    uint32_t off[PER_WAVE];
+    __device__ __forceinline__ void init(int w, int ld) {
+        const int L = threadIdx.x & 63;
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; i++) {
+            const int row = (w * PER_WAVE + i) * (1024 / Tile<D>::ROWB) + L / Tile<D>::CPR;
+            const int logical = (L % Tile<D>::CPR) ^ Tile<D>::swz(row);
+            off[i] = ((uint32_t)row * (uint32_t)ld + (uint32_t)(logical * 8)) * 2u;
+            asm volatile("" : "+v"(off[i]));   // keep it in its register: cheaper than recomputing it at every use
+        }
+    }
+    // lds_tile, w and base are wave-uniform
+    __device__ __forceinline__ void issue(uint32_t lds_tile, i32x4 rs, int w, uint32_t base) const {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; i++) {
+            const uint32_t dst = lds_tile + (uint32_t)(w * PER_WAVE + i) * 1024u;
+            const uint32_t voff = off[i] + base;
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(dst), "v"(voff), "s"(rs) : "memory");
+        }
+    }
+};
+
+// Slots [I0, I1) of a stream of N MFMA slots: slot i requests the fragment of slot i + AHEAD from LDS, issues
+// its MFMA and then the vector work `side(i)`, which the same wave issues while that MFMA occupies the matrix
+// pipe; the fence after each slot keeps this order.  A call starts its own lookahead (slots I0 .. I0+AHEAD-1).
+template <int I0, int I1, int N, int AHEAD, typename L, typename M, typename W>
+__device__ __forceinline__ void mfma_stream(L load, M mma, W side) {
+    bf16x8 f[N];
+#pragma unroll
+    for (int i = I0; i < I0 + AHEAD && i < I1; i++) f[i] = load(i);
+#pragma unroll
+    for (int i = I0; i < I1; i++) {
+        if (i + AHEAD < I1) f[i + AHEAD] = load(i + AHEAD);
+        mma(i, f[i]);
+        side(i);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // ------------------------------------------------------------------ forward
 // NPAR = 1: 4 waves, each 32 queries of the block's 128, walking the key tiles one by one.
 // NPAR = 2: 8 waves; waves 4..7 repeat the queries of waves 0..3 and the two groups take the even and the odd
 //   key tiles (two tiles per step), so the longest job of the launch -- the last query block -- is half as
-//   long and the two waves of a SIMD overlap each other's MFMA and softmax phases.  The two partial results
-//   (accumulator, running maximum, sum) are merged through LDS at the end, always in the same order.
+//   long.  The two partial results (accumulator, running maximum, sum) are merged through LDS at the end,
+//   always in the same order.
 template <int D, int NPAR>
 __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                        bf16_t* __restrict__ o, float* __restrict__ lse, int S, int nh, int nkv, int B) {
     using TL = Tile<D>;
-    constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
-    extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
+    constexpr int NW = 4 * NPAR;
+    constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
+    extern __shared__ __attribute__((aligned(1024))) char smem[];     // [wave group][stage][K|V]
     // flattened grid, last query block first: the long jobs of every head and sample are dispatched
     // before the short ones
     const int nhb = nh * B;
     const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
     const int A = nh * D;
     const int kcol = A + (h / (nh / nkv)) * D;   // this query head's key head; its value head is nkv*D further
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, hf = lane >> 5;
     const int wq = wave & 3, par = wave >> 2;
     const int q0 = qb * 128 + wq * 32;
     const int query = q0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
     const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    const typename TL::Offsets offs = TL::offsets();
-    // step s brings key tiles NPAR*s .. NPAR*s + NPAR-1
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
+    DmaLane<D, NW> dl_;
+    dl_.init(wave, ld);
+    // step s brings key tiles NPAR*s .. NPAR*s + NPAR-1, tile p of them into wave group p's stage s&1
     auto issue = [&](int st, int s) {
 #pragma unroll
         for (int p = 0; p < NPAR; p++) {
-            const uint32_t kv = (uint32_t)(NPAR * s + p) * 64u;
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, kcol);
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, kcol + nkv * D);
+            const uint32_t row0 = (tokb + (uint32_t)(NPAR * s + p) * 64u) * (uint32_t)ld;
+            const uint32_t dst = lds0 + (uint32_t)((2 * p + st) * STAGE);
+            dl_.issue(dst, rsw, wave, (row0 + (uint32_t)kcol) * 2u);
+            dl_.issue(dst + TL::BYTES, rsw, wave, (row0 + (uint32_t)(kcol + nkv * D)) * 2u);
         }
     };
     issue(0, 0);
+    FragAddr<D> fa;
+    fa.init(lds0 + (uint32_t)(par * 2 * STAGE));
 
     bf16x8 qf[D / 16];
     load_qfrag<D>(qf, rs, tokb + query, ld, h * D);
@@ -193,6 +244,10 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
         for (int r = 0; r < 16; r++) oacc[i][r] = 0.f;
     float m = -INFINITY, lsum = 0.f;
     const float c = LOG2E / sqrtf((float)D);
+    // the register loads above are complete here, as far as the compiler's wait counters go: the loop must not
+    // carry waits for them, because those would also wait for the tile loads in flight
+#pragma unroll
+    for (int kk = 0; kk < D / 16; kk++) asm volatile("" : "+v"(qf[kk]));
 
     const int q_last = min(qb * 128 + 127, S - 1);
     for (int s = 0; s * (64 * NPAR) <= q_last; s++) {
@@ -200,14 +255,13 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
         __syncthreads();   // the tiles of step s are in LDS for everyone; everyone has finished with step s-1
         if ((s + 1) * (64 * NPAR) <= q_last) issue((s + 1) & 1, s + 1);
         const int kv0 = (NPAR * s + par) * 64;
-        const char* sK = smem + (s & 1) * STAGE + par * 2 * TL::BYTES;
-        const char* sV = sK + TL::BYTES;
+        if (s) fa.shift((s & 1) ? STAGE : -STAGE);
         if (kv0 > q0 + 31) continue;  // every key of the tile lies after every query of this wave
         f32x16 sacc[2];
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         // S^T = K Q^T: index -> (key half tl, k step kk); the first k step starts from a zero accumulator
         mfma_pipeline<2 * (D / 16) / 4, 4>(
-            [&](int idx) { return TL::frag_rows(sK, offs, idx / (D / 16), idx % (D / 16)); },
+            [&](int idx) { return fa.frag_rows(0, idx / (D / 16), idx % (D / 16)); },
             [&](int idx, bf16x8 f) {
                 const int tl = idx / (D / 16), kk = idx % (D / 16);
                 sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], kk ? sacc[tl] : zero16, 0, 0, 0);
@@ -256,7 +310,7 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
         for (int kk = 0; kk < 4; kk++) pf[kk] = pack8(sacc[kk >> 1], kk & 1);
         // O^T += V^T P^T: index -> (key step kk, channel block dt)
         mfma_pipeline<4 * (D / 32) / 4, 4>(
-            [&](int idx) { return TL::frag_cols(sV, offs, idx % (D / 32), idx / (D / 32)); },
+            [&](int idx) { return fa.frag_cols(TL::BYTES, idx % (D / 32), idx / (D / 32)); },
             [&](int idx, bf16x8 f) {
                 const int kk = idx / (D / 32), dt = idx % (D / 32);
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[kk], oacc[dt], 0, 0, 0);
@@ -305,50 +359,58 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
 }
 
 // --------------------------------------------------------------- backward: dQ
-// NPAR as in k_attn_fwd: with 2, the even and the odd key tiles go to two groups of 4 waves whose dQ sums
-// are added through LDS at the end.  The kernel also forms delta = <dO, O> of its queries (each lane holds
-// half a row of dO for the MFMAs anyway) and leaves it in dvec for the dK/dV kernel that follows.
-template <int D, int NPAR>
-__global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
-                                                          const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, uint32_t do_bytes,
-                                                          const float* __restrict__ lse, float* __restrict__ dvec,
-                                                          bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
+// The job of query block qb of (head, sample) hb = h + nh*b.  NPAR as in k_attn_fwd: with 2, the even and the
+// odd key tiles go to two groups of 4 waves whose dQ sums are added through LDS at the end.  Unless DELTA_GIVEN
+// (dvec filled by k_attn_delta before), the job also forms delta = <dO, O> of its queries (each lane holds half a
+// row of dO for the MFMAs anyway) and leaves it in dvec for the dK/dV kernel that follows.
+// LDS: per wave group, two stages of (K tile | V tile).
+template <int D, int NPAR, bool DELTA_GIVEN>
+__device__ __forceinline__ void attn_bwd_dq_body(const int qb, const int hb, const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+                                                 const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                 const float* __restrict__ lse, float* __restrict__ dvec,
+                                                 bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
     using TL = Tile<D>;
-    constexpr int STAGE = NPAR * 2 * TL::BYTES;                       // NPAR x (K tile | V tile)
-    extern __shared__ __attribute__((aligned(1024))) char smem[];     // two stages
-    const int nhb = nh * B;   // flattened grid, last query block first (see k_attn_fwd)
-    const int qb = (int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), h = (blockIdx.x % nhb) % nh, b = (blockIdx.x % nhb) / nh;
+    constexpr int NW = 4 * NPAR;
+    constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
+    extern __shared__ __attribute__((aligned(1024))) char smem[];     // [wave group][stage][K|V]
+    const int h = hb % nh, b = hb / nh;
     const int A = nh * D;
     const int kcol = A + (h / (nh / nkv)) * D;   // this query head's key head; its value head is nkv*D further
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, hf = lane >> 5;
     const int wq = wave & 3, par = wave >> 2;
     const int q0 = qb * 128 + wq * 32;
     const int query = q0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
     const __amdgpu_buffer_rsrc_t rsdo = make_rsrc(dout, do_bytes);
-    const __amdgpu_buffer_rsrc_t rso = make_rsrc(o, do_bytes);
     const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    const typename TL::Offsets offs = TL::offsets();
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
+    DmaLane<D, NW> dl_;
+    dl_.init(wave, ld);
+    // step s brings key tiles NPAR*s .. NPAR*s + NPAR-1, tile p of them into wave group p's stage s&1
     auto issue = [&](int st, int s) {
 #pragma unroll
         for (int p = 0; p < NPAR; p++) {
-            const uint32_t kv = (uint32_t)(NPAR * s + p) * 64u;
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES, rsw, tokb + kv, ld, kcol);
-            TL::template dma<4 * NPAR>(lds0 + st * STAGE + p * 2 * TL::BYTES + TL::BYTES, rsw, tokb + kv, ld, kcol + nkv * D);
+            const uint32_t row0 = (tokb + (uint32_t)(NPAR * s + p) * 64u) * (uint32_t)ld;
+            const uint32_t dst = lds0 + (uint32_t)((2 * p + st) * STAGE);
+            dl_.issue(dst, rsw, wave, (row0 + (uint32_t)kcol) * 2u);
+            dl_.issue(dst + TL::BYTES, rsw, wave, (row0 + (uint32_t)(kcol + nkv * D)) * 2u);
         }
     };
     issue(0, 0);
+    FragAddr<D> fa;
+    fa.init(lds0 + (uint32_t)(par * 2 * STAGE));
 
     bf16x8 qf[D / 16], dof[D / 16];
     load_qfrag<D>(qf, rs, tokb + query, ld, h * D);
     load_qfrag<D>(dof, rsdo, tokb + query, A, h * D);
     const float sc = 1.0f / sqrtf((float)D);
     const float c = LOG2E * sc;
-    // delta: this lane's half of the row, plus the other half from lane ^ 32
+    // delta: this lane's half of the row, plus the other half from lane ^ 32 (or, when a kernel before this one
+    // has left it in dvec, read from there)
     float dl = 0.f;
-    {
+    if (!DELTA_GIVEN) {
+        const __amdgpu_buffer_rsrc_t rso = make_rsrc(o, do_bytes);
         bf16x8 of[D / 16];
         load_qfrag<D>(of, rso, tokb + query, A, h * D);
 #pragma unroll
@@ -361,55 +423,93 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd
     if (query < S) {
         const size_t at = ((size_t)b * nh + h) * S + query;
         L = lse[at] * LOG2E;
-        if (par == 0 && hf == 0) dvec[at] = dl;
+        if (DELTA_GIVEN) dl = dvec[at];
+        else if (par == 0 && hf == 0) dvec[at] = dl;
     }
+    // every register load above is complete here, as far as the compiler's wait counters go: the loop must not
+    // carry waits for them, because those would also wait for the tile loads in flight
+#pragma unroll
+    for (int kk = 0; kk < D / 16; kk++) asm volatile("" : "+v"(qf[kk]), "+v"(dof[kk]));
+    asm volatile("" : "+v"(L), "+v"(dl));
     f32x16 dq[D / 32];
 #pragma unroll
     for (int i = 0; i < D / 32; i++)
 #pragma unroll
         for (int r = 0; r < 16; r++) dq[i][r] = 0.f;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+    // One key tile (64 keys) against this wave's 32 queries.  MFMA slots, K = D/16 k steps:
+    //   [0, 2K)   S^T and dP^T of keys 0..31   (K Q^T, V dO^T; k step i/2, alternating)
+    //   [2K, 4K)  the same for keys 32..63, with the softmax-gradient arithmetic of keys 0..31 in the shadow
+    //   then      dQ^T += K^T dS^T over key steps 0,1 (keys 0..31), with the arithmetic of keys 32..63 in the
+    //             shadow, and over key steps 2,3.
+    // On a tile that touches the diagonal, the entries of keys after the query are cleared in the packed dS^T.
     const int q_last = min(qb * 128 + 127, S - 1);
     for (int s = 0; s * (64 * NPAR) <= q_last; s++) {
         wait_dma();
         __syncthreads();   // the tiles of step s are in LDS for everyone; everyone has finished with step s-1
         if ((s + 1) * (64 * NPAR) <= q_last) issue((s + 1) & 1, s + 1);
         const int kv0 = (NPAR * s + par) * 64;
-        const char* sK = smem + (s & 1) * STAGE + par * 2 * TL::BYTES;
-        const char* sV = sK + TL::BYTES;
+        if (s) fa.shift((s & 1) ? STAGE : -STAGE);
         if (kv0 > q0 + 31) continue;
-        f32x16 sacc[2], pacc[2];
-        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        // S^T = K Q^T and dP^T = V dO^T: index -> (k step kk, {K half 0, K half 1, V half 0, V half 1})
-        mfma_pipeline<D / 16, 4>(
-            [&](int idx) { return TL::frag_rows((idx & 2) ? sV : sK, offs, idx & 1, idx >> 2); },
-            [&](int idx, bf16x8 f) {
-                const int kk = idx >> 2, tl = idx & 1;
-                if (idx & 2) pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dof[kk], kk ? pacc[tl] : zero16, 0, 0, 0);
-                else sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], kk ? sacc[tl] : zero16, 0, 0, 0);
-            });
         const bool diag = kv0 + 63 > q0;
+        constexpr int K2 = 2 * (D / 16), NQ = 4 * (D / 32);
+        f32x16 sacc[2], pacc[2];
+        union { uint32_t u[4]; bf16x8 v; } sf[4];
+        const int qrel = query - kv0 - 4 * hf;      // a register's key offset inside the tile (without its lane part) that equals the query
+        auto grad = [&](int tl, int r) {            // element r of key half tl: p, then dS^T (before the 1/sqrt(d) factor)
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[tl][r], c, -L));
+            sacc[tl][r] = p * (pacc[tl][r] - dl);
+            if (r & 1) sf[2 * tl + (r >> 3)].u[(r & 7) >> 1] = pack_bf2(sacc[tl][r - 1], sacc[tl][r]);
+        };
+        auto clear_future = [&](int tl, int r0) {   // packed pairs (r-1, r), r0 <= r < r0+8, of key half tl: drop keys after the query
+            asm volatile("" ::: "memory");          // a real branch around the rare case, not selects on every tile
 #pragma unroll
-        for (int tl = 0; tl < 2; tl++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                float p = __builtin_amdgcn_exp2f(sacc[tl][r] * c - L);
-                if (diag) {
-                    const int key = kv0 + 32 * tl + 8 * (r >> 2) + 4 * hf + (r & 3);
-                    if (key > query) p = 0.f;
-                }
-                sacc[tl][r] = p * (pacc[tl][r] - dl);  // dS^T (before the 1/sqrt(d) factor)
+            for (int r = r0 + 1; r < r0 + 8; r += 2) {
+                const int k1 = 32 * tl + 8 * (r >> 2) + (r & 3);    // key offset of element r; element r-1 is the key before it
+                uint32_t& w = sf[2 * tl + (r >> 3)].u[(r & 7) >> 1];
+                w = k1 <= qrel ? w : (k1 - 1 <= qrel ? (w & 0xFFFFu) : 0u);
             }
-        bf16x8 sf[4];
+        };
+        auto load = [&](int i) {
+            if (i < 2 * K2) return fa.frag_rows((i & 1) ? TL::BYTES : 0, i / K2, (i % K2) >> 1);
+            const int j = i - 2 * K2;
+            return fa.frag_cols(0, j % (D / 32), j / (D / 32));
+        };
+        auto mma = [&](int i, bf16x8 f) {
+            if (i < 2 * K2) {
+                const int tl = i / K2, kk = (i % K2) >> 1;
+                if (i & 1) pacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dof[kk], kk ? pacc[tl] : zero16, 0, 0, 0);
+                else sacc[tl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[kk], kk ? sacc[tl] : zero16, 0, 0, 0);
+            } else {
+                const int j = i - 2 * K2, kk = j / (D / 32), dt = j % (D / 32);
+                dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk].v, dq[dt], 0, 0, 0);
+            }
+        };
+        // slots [0, 2K2): S^T, dP^T of both halves; the arithmetic of half 0 rides on the second K2 slots
+        constexpr int PER0 = (16 + K2 - 1) / K2;
+        mfma_stream<0, 2 * K2, 2 * K2 + NQ, 2>(load, mma, [&](int i) {
+            if (i >= K2) {
 #pragma unroll
-        for (int kk = 0; kk < 4; kk++) sf[kk] = pack8(sacc[kk >> 1], kk & 1);
-        // dQ^T += K^T dS^T: index -> (key step kk, channel block dt)
-        mfma_pipeline<4 * (D / 32) / 4, 4>(
-            [&](int idx) { return TL::frag_cols(sK, offs, idx % (D / 32), idx / (D / 32)); },
-            [&](int idx, bf16x8 f) {
-                const int kk = idx / (D / 32), dt = idx % (D / 32);
-                dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk], dq[dt], 0, 0, 0);
-            });
+                for (int e = 0; e < PER0; e++) { const int r = (i - K2) * PER0 + e; if (r < 16) grad(0, r); }
+            }
+        });
+        if (diag) { clear_future(0, 0); clear_future(0, 8); }
+        // slots of dQ^T: key steps 0,1 with the first half of the arithmetic of key half 1 (8 elements), key step 2
+        // with the second, key step 3
+        constexpr int DT = D / 32;
+        constexpr int PERA = (8 + 2 * DT - 1) / (2 * DT), PERB = (8 + DT - 1) / DT;
+        mfma_stream<2 * K2, 2 * K2 + 2 * DT, 2 * K2 + NQ, 2>(load, mma, [&](int i) {
+#pragma unroll
+            for (int e = 0; e < PERA; e++) { const int r = (i - 2 * K2) * PERA + e; if (r < 8) grad(1, r); }
+        });
+        if (diag) clear_future(1, 0);
+        mfma_stream<2 * K2 + 2 * DT, 2 * K2 + 3 * DT, 2 * K2 + NQ, 2>(load, mma, [&](int i) {
+#pragma unroll
+            for (int e = 0; e < PERB; e++) { const int r = 8 + (i - 2 * K2 - 2 * DT) * PERB + e; if (r < 16) grad(1, r); }
+        });
+        if (diag) clear_future(1, 8);
+        mfma_stream<2 * K2 + 3 * DT, 2 * K2 + NQ, 2 * K2 + NQ, 2>(load, mma, [&](int) {});
     }
     if (NPAR == 2) {
         __syncthreads();   // nobody reads a K/V tile any more and no DMA is in flight
@@ -442,17 +542,17 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd
 }
 
 // ----------------------------------------------------------- backward: dK, dV
-// 8 waves: wave = (query half qh, key group kw).  A workgroup owns 128 keys (4 groups of 32) and walks
-// the query tiles from its diagonal to the end; of every 64-query tile a wave takes the 32 queries of
-// its half, so two waves per SIMD overlap each other's MFMA and softmax phases.  The two halves' dK, dV
+// The job of key block kb; rem = (sample, key/value head, slice of its query heads).  8 waves: wave = (query
+// half qh, key group kw).  The workgroup owns 128 keys (4 groups of 32) and walks the query tiles from its
+// diagonal to the end; of every 64-query tile a wave takes the 32 queries of its half.  The two halves' dK, dV
 // sums are added through LDS at the end (fixed order: deterministic).
 constexpr int KVTHREADS = 512;
 template <int D>
-__global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
-                                                            const bf16_t* __restrict__ dout, uint32_t do_bytes,
-                                                            const float* __restrict__ lse, const float* __restrict__ dvec,
-                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
-                                                            int hs, float* __restrict__ part) {
+__device__ __forceinline__ void attn_bwd_dkv_body(const int kb, const int rem, const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+                                                  const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                  const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                  bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
+                                                  int hs, float* __restrict__ part) {
     using TL = Tile<D>;
     constexpr int NW = KVTHREADS / WAVE;
     constexpr int STAGE = 2 * TL::BYTES;                              // Q tile | dO tile
@@ -462,8 +562,6 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     float* sLD = reinterpret_cast<float*>(smem + 2 * STAGE + 4 * TL::BYTES);
     // flattened grid over (key block, sample, key/value head, slice of its query heads): key block first (block 0
     // has the most query tiles), so the long jobs of every head and sample are dispatched before the short ones
-    const int nkb = nkv * hs * B;
-    const int kb = blockIdx.x / nkb, rem = blockIdx.x % nkb;
     const int b = rem / (nkv * hs), hk = (rem % (nkv * hs)) / hs, ps = rem % hs;
     // the key/value head collects the gradients of query heads hk*(nh/nkv) .. ; this workgroup sums G of them
     // (slice ps of hs) and, when hs > 1, leaves fp32 partial sums in part[ps][dK|dV][token][nkv*D]
@@ -473,18 +571,20 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     const int k0 = kb * 128 + kw * 32;
     const int key = k0 + (lane & 31);
     const uint32_t tokb = (uint32_t)b * S;
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, qkv_bytes);
     const i32x4 rsw = make_rsrc_words(qkv, qkv_bytes);
     const i32x4 rswdo = make_rsrc_words(dout, do_bytes);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    const typename TL::Offsets offs = TL::offsets();
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    DmaLane<D, NW> lane_q, lane_o;            // rows of ld elements (q | k | v) and of A elements (dO)
+    lane_q.init(wave_s, ld);
+    lane_o.init(wave_s, A);
     // work items: for each of the G query heads, the query tiles from the key block's diagonal to the end;
     // an item is (query head h, step s) with its 64 queries starting at kb*128 + 64*s
     const int nsteps = (S - kb * 128 + 63) / 64, nitems = G * nsteps;
     auto issue = [&](int st, int h, int sq) {
-        const int q = kb * 128 + sq * 64;
-        TL::template dma<NW>(lds0 + st * STAGE, rsw, tokb + q, ld, h * D);
-        TL::template dma<NW>(lds0 + st * STAGE + TL::BYTES, rswdo, tokb + q, A, h * D);
+        const uint32_t row0 = tokb + (uint32_t)(kb * 128 + sq * 64);
+        lane_q.issue(lds0 + st * STAGE, rsw, wave_s, (row0 * (uint32_t)ld + (uint32_t)(h * D)) * 2u);
+        lane_o.issue(lds0 + st * STAGE + TL::BYTES, rswdo, wave_s, (row0 * (uint32_t)A + (uint32_t)(h * D)) * 2u);
     };
     // lse (log2 domain) and delta of the 64 queries of an item: thread i < 64 -> lse, 64 <= i < 128 -> delta
     auto stat = [&](int h, int sq) -> float {
@@ -496,15 +596,19 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     // K, V of keys kb*128 .. +127: resident for the whole kernel (first wait_dma below covers them)
 #pragma unroll
     for (int i = 0; i < 2; i++) {
-        TL::template dma<NW>(lds0 + 2 * STAGE + i * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + hk * D);
-        TL::template dma<NW>(lds0 + 2 * STAGE + (2 + i) * TL::BYTES, rsw, tokb + kb * 128 + 64 * i, ld, A + (nkv + hk) * D);
+        const uint32_t row0 = (tokb + (uint32_t)(kb * 128 + 64 * i)) * (uint32_t)ld;
+        lane_q.issue(lds0 + 2 * STAGE + i * TL::BYTES, rsw, wave_s, (row0 + (uint32_t)(A + hk * D)) * 2u);
+        lane_q.issue(lds0 + 2 * STAGE + (2 + i) * TL::BYTES, rsw, wave_s, (row0 + (uint32_t)(A + (nkv + hk) * D)) * 2u);
     }
     issue(0, h_first, 0);
     float nstat = stat(h_first, 0);
     int cs = 0;                                            // step of the item being worked on
     int ih = nsteps > 1 ? h_first : h_first + 1, is = nsteps > 1 ? 1 : 0;   // the item after it
-    const char* sKw = sKV + (kw >> 1) * TL::BYTES;        // tile holding this wave's 32 keys (row block kw & 1)
-    const char* sVw = sKw + 2 * TL::BYTES;
+    // fragment addresses: fq of the stage tiles (Q at +0, dO at +BYTES; moved to the other stage after every
+    // item), fk of this wave's 32 keys in the resident K tile (V at +2*BYTES)
+    FragAddr<D> fq, fk;
+    fq.init(lds0 + (uint32_t)(qh * 32 * TL::ROWB));   // this wave's 32 queries of a tile: row block qh = key steps 2qh, 2qh+1
+    fk.init(lds0 + (uint32_t)(2 * STAGE + (kw >> 1) * TL::BYTES + (kw & 1) * 32 * TL::ROWB));
     const float sc = 1.0f / sqrtf((float)D);
     const float c = LOG2E * sc;
     f32x16 dk[D / 32], dv[D / 32];
@@ -519,8 +623,7 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
         wait_dma();
         __syncthreads();   // item t and its lse/delta are in LDS for everyone; everyone has finished with item t-1
         if (t + 1 < nitems) { issue((t + 1) & 1, ih, is); nstat = stat(ih, is); }
-        const char* sQ = smem + (t & 1) * STAGE;
-        const char* sO = sQ + TL::BYTES;
+        if (t) fq.shift((t & 1) ? STAGE : -STAGE);
         const float* sL = sLD + (t & 1) * 128;
         const float* sD = sL + 64;
         const int q0 = qt + 32 * qh;                 // this wave's 32 queries of the tile
@@ -534,8 +637,8 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
             mfma_pipeline<4 * (D / 16) / 4, 4>(
                 [&](int idx) {
                     const int kk = idx >> 2, w = idx & 3;
-                    return w == 0 ? TL::frag_rows(sQ, offs, qh, kk) : w == 1 ? TL::frag_rows(sKw, offs, kw & 1, kk)
-                         : w == 2 ? TL::frag_rows(sO, offs, qh, kk) : TL::frag_rows(sVw, offs, kw & 1, kk);
+                    return w == 0 ? fq.frag_rows(0, 0, kk) : w == 1 ? fk.frag_rows(0, 0, kk)
+                         : w == 2 ? fq.frag_rows(TL::BYTES, 0, kk) : fk.frag_rows(2 * TL::BYTES, 0, kk);
                 },
                 [&](int idx, bf16x8 f) {
                     const int w = idx & 3, kk = idx >> 2;
@@ -544,36 +647,44 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
                     else pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, f, kk ? pacc : zero16, 0, 0, 0);
                 });
         }
-        const bool edge = (q0 < k0 + 31) || (q0 + 31 >= S);
+        union { uint32_t u[4]; bf16x8 v; } pf[2], sf[2];
 #pragma unroll
         for (int g = 0; g < 4; g++) {
             const int qi = 32 * qh + 8 * g + 4 * hf;
             const float4 l4 = *reinterpret_cast<const float4*>(&sL[qi]);
             const float4 d4 = *reinterpret_cast<const float4*>(&sD[qi]);
             const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+            float pv[4], sv[4];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                const int r = 4 * g + e;
-                float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c, -ls[e]));
-                if (edge) {
-                    const int q = qt + qi + e;
-                    if (key > q || q >= S) p = 0.f;
-                }
-                sacc[r] = p;
-                pacc[r] = p * (pacc[r] - ds[e]);
+                pv[e] = __builtin_amdgcn_exp2f(fmaf(sacc[4 * g + e], c, -ls[e]));
+                sv[e] = pv[e] * (pacc[4 * g + e] - ds[e]);
+            }
+            pf[g >> 1].u[2 * (g & 1)] = pack_bf2(pv[0], pv[1]);
+            pf[g >> 1].u[2 * (g & 1) + 1] = pack_bf2(pv[2], pv[3]);
+            sf[g >> 1].u[2 * (g & 1)] = pack_bf2(sv[0], sv[1]);
+            sf[g >> 1].u[2 * (g & 1) + 1] = pack_bf2(sv[2], sv[3]);
+        }
+        if ((q0 < k0 + 31) || (q0 + 31 >= S)) {
+            // the tile touches the diagonal or the end of the sequence: clear the entries whose query precedes the
+            // key or does not exist (a real branch around the rare case, not selects on every tile)
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int w = 0; w < 8; w++) {
+                const int q = q0 + 8 * (w >> 1) + 4 * hf + 2 * (w & 1);   // query of the pair's first element
+                const uint32_t keep = (key <= q && q < S ? 0xFFFFu : 0u) | (key <= q + 1 && q + 1 < S ? 0xFFFF0000u : 0u);
+                pf[w >> 2].u[w & 3] &= keep;
+                sf[w >> 2].u[w & 3] &= keep;
             }
         }
-        bf16x8 pf[2], sf[2];
-#pragma unroll
-        for (int kk = 0; kk < 2; kk++) { pf[kk] = pack8(sacc, kk); sf[kk] = pack8(pacc, kk); }
         // dV^T += dO^T P and dK^T += Q^T dS over this wave's 32 queries (k steps 2qh, 2qh+1 of the tile):
         // index -> (query step, channel block dt, {dO, Q})
         mfma_pipeline<2 * (D / 32) * 2 / 4, 4>(
-            [&](int idx) { return TL::frag_cols((idx & 1) ? sQ : sO, offs, (idx >> 1) % (D / 32), 2 * qh + (idx >> 1) / (D / 32)); },
+            [&](int idx) { return fq.frag_cols((idx & 1) ? 0 : TL::BYTES, (idx >> 1) % (D / 32), (idx >> 1) / (D / 32)); },
             [&](int idx, bf16x8 f) {
                 const int dt = (idx >> 1) % (D / 32), kk = (idx >> 1) / (D / 32);
-                if (idx & 1) dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk], dk[dt], 0, 0, 0);
-                else dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[kk], dv[dt], 0, 0, 0);
+                if (idx & 1) dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, sf[kk].v, dk[dt], 0, 0, 0);
+                else dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[kk].v, dv[dt], 0, 0, 0);
             });
     }
     // add the second query half's sums to the first's: [kw][register][lane] floats in the stage memory
@@ -657,6 +768,77 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
     }
 }
 
+// flattened grid, last query block first (see k_attn_fwd)
+template <int D, int NPAR>
+__global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+                                                          const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                          const float* __restrict__ lse, float* __restrict__ dvec,
+                                                          bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
+    const int nhb = nh * B;
+    attn_bwd_dq_body<D, NPAR, false>((int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), blockIdx.x % nhb, qkv, ld, qkv_bytes, o, dout, do_bytes,
+                                     lse, dvec, dqkv, S, nh, nkv, B);
+}
+
+// flattened grid over (key block, sample, key/value head, slice of its query heads): key block first (block 0
+// has the most query tiles), so the long jobs of every head and sample are dispatched before the short ones
+template <int D>
+__global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+                                                            const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                            const float* __restrict__ lse, const float* __restrict__ dvec,
+                                                            bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
+                                                            int hs, float* __restrict__ part) {
+    const int nkb = nkv * hs * B;
+    attn_bwd_dkv_body<D>(blockIdx.x / nkb, blockIdx.x % nkb, qkv, ld, qkv_bytes, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B, hs, part);
+}
+
+// Both backward passes in one launch, for launches so small that each pass alone is bound by its longest job (the
+// last query block, the first key block) while most CUs idle: the jobs of the two passes are dealt out together,
+// longest first -- level l holds the dK/dV jobs of key block l and then the dQ jobs of query block n-1-l -- so the
+// short jobs of one pass fill the CUs that the other leaves.  delta comes from k_attn_delta, launched before.
+template <int D>
+__global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_both(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
+                                                             const bf16_t* __restrict__ dout, uint32_t do_bytes,
+                                                             const float* __restrict__ lse, float* __restrict__ dvec,
+                                                             bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
+                                                             int hs, float* __restrict__ part) {
+    const int nkvj = nkv * hs * B, nqj = nh * B, per = nkvj + nqj;
+    const int level = blockIdx.x / per, nblk = gridDim.x / per;
+    const int r = blockIdx.x % per;
+    if (r < nkvj) attn_bwd_dkv_body<D>(level, r, qkv, ld, qkv_bytes, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B, hs, part);
+    else attn_bwd_dq_body<D, 2, true>(nblk - 1 - level, r - nkvj, qkv, ld, qkv_bytes, nullptr, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B);
+}
+
+// delta[b, h, s] = <dO[s, h, :], O[s, h, :]>.  Two threads per (token, head): thread hf takes the 8-channel groups
+// 16kk + 8hf .. of the row, in the order and with the arithmetic of the dQ kernel's own delta.
+template <int D>
+__global__ __launch_bounds__(256) void k_attn_delta(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, float* __restrict__ dvec,
+                                                    int S, int nh, long rows) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long row = i >> 1;                    // token * nh + head
+    const int hf = (int)(i & 1);
+    float dl = 0.f;
+    if (row < rows) {
+        const bf16_t* po = o + row * D + 8 * hf;
+        const bf16_t* pd = dout + row * D + 8 * hf;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; kk++) {
+            const uint4 a = *reinterpret_cast<const uint4*>(pd + 16 * kk), c = *reinterpret_cast<const uint4*>(po + 16 * kk);
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, cw[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                dl = fmaf(lo_bf(aw[e]), lo_bf(cw[e]), dl);
+                dl = fmaf(hi_bf(aw[e]), hi_bf(cw[e]), dl);
+            }
+        }
+    }
+    dl += __shfl_xor(dl, 1, WAVE);
+    if (row < rows && hf == 0) {
+        const long tok = row / nh;
+        const int h = (int)(row % nh);
+        dvec[((tok / S) * nh + h) * S + tok % S] = dl;
+    }
+}
+
 // Sums the hs partial dK and dV planes of grouped heads in a fixed order and writes them, rounded to bf16,
 // into the k and v columns of dqkv.  A thread owns 4 consecutive channels of one token.
 __global__ __launch_bounds__(256) void k_attn_dkv_reduce(const float* __restrict__ part, int hs, long tokens, int Akv,
@@ -735,20 +917,21 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
     if (hs > 1 && !scratch) return hipErrorInvalidValue;
     const unsigned grid_kv = (unsigned)((S + 127) / 128) * nkv * hs * B;
     if (split_keys(grid, S)) {
-        constexpr int LDS = 8 * Tile<D>::BYTES;
-        e = set_lds(k_attn_bwd_dq<D, 2>, LDS);
+        e = set_lds(k_attn_bwd_both<D>, LDS_KV);
         if (e != hipSuccess) return e;
-        k_attn_bwd_dq<D, 2><<<grid, 2 * ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)o, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                             (bf16_t*)dqkv, S, nh, nkv, B);
+        const long rows = (long)B * S * nh;
+        k_attn_delta<D><<<(unsigned)((2 * rows + 255) / 256), 256, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, S, nh, rows);
+        k_attn_bwd_both<D><<<grid + grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
+                                                                      (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch);
     } else {
         constexpr int LDS = 4 * Tile<D>::BYTES;
         e = set_lds(k_attn_bwd_dq<D, 1>, LDS);
         if (e != hipSuccess) return e;
         k_attn_bwd_dq<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)o, (const bf16_t*)dout, do_bytes, lse, dvec,
                                                          (bf16_t*)dqkv, S, nh, nkv, B);
+        k_attn_bwd_dkv<D><<<grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
+                                                              dvec, (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch);
     }
-    k_attn_bwd_dkv<D><<<grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
-                                                          dvec, (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch);
     if (hs > 1) {
         const long n = (long)B * S * (nkv * D / 4);
         k_attn_dkv_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(scratch, hs, (long)B * S, nkv * D, (bf16_t*)dqkv, ld, nh * D);
