@@ -122,12 +122,12 @@ def main():
     wst, gst = [l.wstruct for l in layers], [l.gstruct for l in layers]
     st = L.stream_ptr()
 
-    def step():
+    def step(stream=st):
         # steady-state training: gradients accumulate, nothing is zeroed inside the timed region
         if live == M:
-            hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
+            hh.hh_stage_step(ctx, cfg, wst, xs, ys, dys, dxs, gst, 0, pool, wsp, stream)
         else:
-            hh.hh_stage_step_1f1b(ctx, cfg, wst, live, xs, ys, dys, dxs, gst, 0, pool, wsp, st)
+            hh.hh_stage_step_1f1b(ctx, cfg, wst, live, xs, ys, dys, dxs, gst, 0, pool, wsp, stream)
 
     if a.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=L.DEV).fill_(1)
@@ -220,11 +220,34 @@ def main():
         err = L.rel_err(L.to_np(ys[0]), yo) if k == 1 else None
         out["parity_y_rel_fro"] = None if err is None else float("%.3e" % err)
     if a.workload == "cfg3" and not a.no_extras:
+        out["graph_replay"] = graph_replay(L, step, a.steps, flop_step)
         out["stage_step_cfg4"] = stage_step_ratio(hh, I, L, ctx, median_ms)
         if not a.no_cpu_baseline:
             out["cpu_baseline_other_configs"] = oracle_times(I)
     print(json.dumps(out), flush=True)
     hh.hh_ctx_destroy(ctx)
+
+
+def graph_replay(L, step, steps, flop_step):
+    """The same step recorded once into a HIP graph on a side stream and replayed `steps` times: what a caller who
+    captures the library's launches saves on launch gaps.  Reported beside the eager figure, never as `value`."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(L.stream_ptr())
+        torch.cuda.synchronize()
+        graph.replay()                               # first replay untimed
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    return {"ms_per_step": round(ms, 4), "steps": steps, "tflops": round(flop_step / (ms * 1e-3) / 1e12, 1)}
 
 
 def stage_step_ratio(hh, I, L, ctx, layer_ms):
