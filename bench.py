@@ -180,10 +180,12 @@ def main():
     if dom is not None and fam[dom][0] > 0:
         launches, dms, dwork = fam[dom]
         achieved = dwork / (dms * 1e-3) / 1e12
+        traffic = measured_traffic(a.workload, dom)
         roofline = {"kernel": "k_gemm_dma (%s; one launch = one GEMM call incl. its k-split tail)" % dom, "bound": "mfma",
                     "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(a.workload, dom),
-                    "traffic_unit": "bytes per launch", "traffic_source": "profiles/" + os.path.basename(TRAFFIC_PROFILE) + " (null: no counter pass on this kernel build)",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                    "traffic_unit": "bytes per launch",
+                    "traffic_source": "profiles/" + os.path.basename(TRAFFIC_PROFILE) + ("" if traffic is not None else " holds no counter pass of this kernel build"),
                     "launches": launches,
                     "avg_launch_ms": round(dms / launches, 4), "flop_per_launch": dwork / launches,
                     "ms_per_step": round(dms / a.steps, 4)}
