@@ -358,6 +358,35 @@ __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_fwd
     }
 }
 
+// Backward of the rotary embedding on a gradient row held the accumulator way (block dt = channels 32dt .. +31,
+// registers 4g+e = channels 8g + 4hf + e of the block): channel i of the first half pairs with i + D/2, which the
+// same lane holds in block dt + D/64.  The pair is rotated by minus the angle of position `pos`
+// (table: cos[rope_seq][D/2] then sin[rope_seq][D/2]), scaled by sc, rounded once and stored.
+template <int D>
+__device__ __forceinline__ void store_rope_bwd(bf16_t* row, const f32x16 (&acc)[D / 32], float sc, int hf, int pos,
+                                                const float* __restrict__ rope, int rope_seq) {
+    constexpr int HB = D / 64;
+    const float* cs = rope + (size_t)pos * (D / 2);
+    const float* sn = cs + (size_t)rope_seq * (D / 2);
+#pragma unroll
+    for (int dt = 0; dt < HB; dt++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            const int i = 32 * dt + 8 * g + 4 * hf;
+            const float4 c4 = *reinterpret_cast<const float4*>(cs + i), s4 = *reinterpret_cast<const float4*>(sn + i);
+            const float c[4] = {c4.x, c4.y, c4.z, c4.w}, sm[4] = {-s4.x, -s4.y, -s4.z, -s4.w};
+            float oa[4], ob[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float a = acc[dt][4 * g + e] * sc, b = acc[dt + HB][4 * g + e] * sc;
+                oa[e] = a * c[e] - b * sm[e];
+                ob[e] = b * c[e] + a * sm[e];
+            }
+            *reinterpret_cast<uint2*>(row + i) = make_uint2(pack_bf2(oa[0], oa[1]), pack_bf2(oa[2], oa[3]));
+            *reinterpret_cast<uint2*>(row + i + D / 2) = make_uint2(pack_bf2(ob[0], ob[1]), pack_bf2(ob[2], ob[3]));
+        }
+}
+
 // --------------------------------------------------------------- backward: dQ
 // The job of query block qb of (head, sample) hb = h + nh*b.  NPAR as in k_attn_fwd: with 2, the even and the
 // odd key tiles go to two groups of 4 waves whose dQ sums are added through LDS at the end.  Unless DELTA_GIVEN
@@ -368,7 +397,8 @@ template <int D, int NPAR, bool DELTA_GIVEN>
 __device__ __forceinline__ void attn_bwd_dq_body(const int qb, const int hb, const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                  const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                  const float* __restrict__ lse, float* __restrict__ dvec,
-                                                 bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
+                                                 bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
+                                                 const float* __restrict__ rope, int rope_seq) {
     using TL = Tile<D>;
     constexpr int NW = 4 * NPAR;
     constexpr int STAGE = 2 * TL::BYTES;                              // K tile | V tile
@@ -529,6 +559,10 @@ __device__ __forceinline__ void attn_bwd_dq_body(const int qb, const int hb, con
     }
     if (query < S) {
         bf16_t* row = dqkv + (size_t)(tokb + query) * ld + h * D;
+        if (rope) {
+            store_rope_bwd<D>(row, dq, sc, hf, query, rope, rope_seq);
+            return;
+        }
 #pragma unroll
         for (int dt = 0; dt < D / 32; dt++)
 #pragma unroll
@@ -552,7 +586,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const int kb, const int rem, c
                                                   const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                   const float* __restrict__ lse, const float* __restrict__ dvec,
                                                   bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
-                                                  int hs, float* __restrict__ part) {
+                                                  int hs, float* __restrict__ part, const float* __restrict__ rope, int rope_seq) {
     using TL = Tile<D>;
     constexpr int NW = KVTHREADS / WAVE;
     constexpr int STAGE = 2 * TL::BYTES;                              // Q tile | dO tile
@@ -758,13 +792,16 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const int kb, const int rem, c
 #pragma unroll
                 for (int e = 0; e < 4; e++) w[e] = dv[dt][4 * g + e] + red[(kw * R + dt * 16 + 4 * g + e) * 64 + lane];
                 uint2 v;
-                v.x = pack_bf2(dk[dt][4 * g] * sc, dk[dt][4 * g + 1] * sc);
-                v.y = pack_bf2(dk[dt][4 * g + 2] * sc, dk[dt][4 * g + 3] * sc);
-                *reinterpret_cast<uint2*>(krow + 32 * dt + 8 * g + 4 * hf) = v;
+                if (!rope) {
+                    v.x = pack_bf2(dk[dt][4 * g] * sc, dk[dt][4 * g + 1] * sc);
+                    v.y = pack_bf2(dk[dt][4 * g + 2] * sc, dk[dt][4 * g + 3] * sc);
+                    *reinterpret_cast<uint2*>(krow + 32 * dt + 8 * g + 4 * hf) = v;
+                }
                 v.x = pack_bf2(w[0], w[1]);
                 v.y = pack_bf2(w[2], w[3]);
                 *reinterpret_cast<uint2*>(vrow + 32 * dt + 8 * g + 4 * hf) = v;
             }
+        if (rope) store_rope_bwd<D>(krow, dk, sc, hf, key, rope, rope_seq);
     }
 }
 
@@ -773,10 +810,11 @@ template <int D, int NPAR>
 __global__ __launch_bounds__(ATHREADS * NPAR, NPAR == 1 ? 2 : 1) void k_attn_bwd_dq(const bf16_t* __restrict__ qkv, int ld, uint32_t qkv_bytes,
                                                           const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                           const float* __restrict__ lse, float* __restrict__ dvec,
-                                                          bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B) {
+                                                          bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
+                                                          const float* __restrict__ rope, int rope_seq) {
     const int nhb = nh * B;
     attn_bwd_dq_body<D, NPAR, false>((int)(gridDim.x / nhb) - 1 - (int)(blockIdx.x / nhb), blockIdx.x % nhb, qkv, ld, qkv_bytes, o, dout, do_bytes,
-                                     lse, dvec, dqkv, S, nh, nkv, B);
+                                     lse, dvec, dqkv, S, nh, nkv, B, rope, rope_seq);
 }
 
 // flattened grid over (key block, sample, key/value head, slice of its query heads): key block first (block 0
@@ -786,9 +824,10 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_dkv(const bf16_t* __rest
                                                             const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                             const float* __restrict__ lse, const float* __restrict__ dvec,
                                                             bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
-                                                            int hs, float* __restrict__ part) {
+                                                            int hs, float* __restrict__ part, const float* __restrict__ rope, int rope_seq) {
     const int nkb = nkv * hs * B;
-    attn_bwd_dkv_body<D>(blockIdx.x / nkb, blockIdx.x % nkb, qkv, ld, qkv_bytes, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B, hs, part);
+    attn_bwd_dkv_body<D>(blockIdx.x / nkb, blockIdx.x % nkb, qkv, ld, qkv_bytes, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B, hs, part,
+                         rope, rope_seq);
 }
 
 // Both backward passes in one launch, for launches so small that each pass alone is bound by its longest job (the
@@ -800,12 +839,13 @@ __global__ __launch_bounds__(KVTHREADS) void k_attn_bwd_both(const bf16_t* __res
                                                              const bf16_t* __restrict__ dout, uint32_t do_bytes,
                                                              const float* __restrict__ lse, float* __restrict__ dvec,
                                                              bf16_t* __restrict__ dqkv, int S, int nh, int nkv, int B,
-                                                             int hs, float* __restrict__ part) {
+                                                             int hs, float* __restrict__ part, const float* __restrict__ rope, int rope_seq) {
     const int nkvj = nkv * hs * B, nqj = nh * B, per = nkvj + nqj;
     const int level = blockIdx.x / per, nblk = gridDim.x / per;
     const int r = blockIdx.x % per;
-    if (r < nkvj) attn_bwd_dkv_body<D>(level, r, qkv, ld, qkv_bytes, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B, hs, part);
-    else attn_bwd_dq_body<D, 2, true>(nblk - 1 - level, r - nkvj, qkv, ld, qkv_bytes, nullptr, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B);
+    if (r < nkvj) attn_bwd_dkv_body<D>(level, r, qkv, ld, qkv_bytes, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B, hs, part, rope, rope_seq);
+    else attn_bwd_dq_body<D, 2, true>(nblk - 1 - level, r - nkvj, qkv, ld, qkv_bytes, nullptr, dout, do_bytes, lse, dvec, dqkv, S, nh, nkv, B,
+                                      rope, rope_seq);
 }
 
 // delta[b, h, s] = <dO[s, h, :], O[s, h, :]>.  Two threads per (token, head): thread hf takes the 8-channel groups
@@ -840,26 +880,52 @@ __global__ __launch_bounds__(256) void k_attn_delta(const bf16_t* __restrict__ o
 }
 
 // Sums the hs partial dK and dV planes of grouped heads in a fixed order and writes them, rounded to bf16,
-// into the k and v columns of dqkv.  A thread owns 4 consecutive channels of one token.
-__global__ __launch_bounds__(256) void k_attn_dkv_reduce(const float* __restrict__ part, int hs, long tokens, int Akv,
-                                                         bf16_t* __restrict__ dqkv, int ld, int A) {
+// into the k and v columns of dqkv.  A thread owns 4 consecutive channels c.. of the first half of one key/value
+// head of one token together with their partners c + D/2, so that it can also take the rotary embedding back
+// out of dK (rope != null: rotation by minus the token's angle; table as in store_rope_bwd).
+__global__ __launch_bounds__(256) void k_attn_dkv_reduce(const float* __restrict__ part, int hs, long tokens, int Akv, int D, int S,
+                                                         bf16_t* __restrict__ dqkv, int ld, int A,
+                                                         const float* __restrict__ rope, int rope_seq) {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int c4 = Akv / 4;
-    if (i >= tokens * c4) return;
-    const long tok = i / c4;
-    const int c = (int)(i % c4) * 4;
+    const int per_tok = Akv / 8, half = D / 2;
+    if (i >= tokens * per_tok) return;
+    const long tok = i / per_tok;
+    const int j = (int)(i % per_tok);
+    const int c = (j % (half / 4)) * 4;                     // channel inside the head's first half
+    const int col = (j / (half / 4)) * D + c;
     const size_t plane = (size_t)tokens * Akv;
-    const float* p = part + (size_t)tok * Akv + c;
-    float4 k = *reinterpret_cast<const float4*>(p), v = *reinterpret_cast<const float4*>(p + plane);
+    const float* p = part + (size_t)tok * Akv + col;
+    float4 k0 = *reinterpret_cast<const float4*>(p), k1 = *reinterpret_cast<const float4*>(p + half);
+    float4 v0 = *reinterpret_cast<const float4*>(p + plane), v1 = *reinterpret_cast<const float4*>(p + plane + half);
     for (int s = 1; s < hs; s++) {
-        const float4 a = *reinterpret_cast<const float4*>(p + (size_t)(2 * s) * plane);
-        const float4 b = *reinterpret_cast<const float4*>(p + (size_t)(2 * s + 1) * plane);
-        k.x += a.x; k.y += a.y; k.z += a.z; k.w += a.w;
-        v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+        const float* q = p + (size_t)(2 * s) * plane;
+        const float4 a0 = *reinterpret_cast<const float4*>(q), a1 = *reinterpret_cast<const float4*>(q + half);
+        const float4 b0 = *reinterpret_cast<const float4*>(q + plane), b1 = *reinterpret_cast<const float4*>(q + plane + half);
+        k0.x += a0.x; k0.y += a0.y; k0.z += a0.z; k0.w += a0.w;
+        k1.x += a1.x; k1.y += a1.y; k1.z += a1.z; k1.w += a1.w;
+        v0.x += b0.x; v0.y += b0.y; v0.z += b0.z; v0.w += b0.w;
+        v1.x += b1.x; v1.y += b1.y; v1.z += b1.z; v1.w += b1.w;
     }
-    bf16_t* row = dqkv + (size_t)tok * ld + A + c;
-    *reinterpret_cast<uint2*>(row) = make_uint2(pack_bf2(k.x, k.y), pack_bf2(k.z, k.w));
-    *reinterpret_cast<uint2*>(row + Akv) = make_uint2(pack_bf2(v.x, v.y), pack_bf2(v.z, v.w));
+    if (rope) {
+        const float* cs = rope + (size_t)(tok % S) * half + c;
+        const float* sn = cs + (size_t)rope_seq * half;
+        const float4 c4 = *reinterpret_cast<const float4*>(cs), s4 = *reinterpret_cast<const float4*>(sn);
+        const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, sm[4] = {-s4.x, -s4.y, -s4.z, -s4.w};
+        const float a[4] = {k0.x, k0.y, k0.z, k0.w}, b[4] = {k1.x, k1.y, k1.z, k1.w};
+        float oa[4], ob[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            oa[e] = a[e] * cc[e] - b[e] * sm[e];
+            ob[e] = b[e] * cc[e] + a[e] * sm[e];
+        }
+        k0 = make_float4(oa[0], oa[1], oa[2], oa[3]);
+        k1 = make_float4(ob[0], ob[1], ob[2], ob[3]);
+    }
+    bf16_t* row = dqkv + (size_t)tok * ld + A + col;
+    *reinterpret_cast<uint2*>(row) = make_uint2(pack_bf2(k0.x, k0.y), pack_bf2(k0.z, k0.w));
+    *reinterpret_cast<uint2*>(row + half) = make_uint2(pack_bf2(k1.x, k1.y), pack_bf2(k1.z, k1.w));
+    *reinterpret_cast<uint2*>(row + Akv) = make_uint2(pack_bf2(v0.x, v0.y), pack_bf2(v0.z, v0.w));
+    *reinterpret_cast<uint2*>(row + Akv + half) = make_uint2(pack_bf2(v1.x, v1.y), pack_bf2(v1.z, v1.w));
 }
 
 // ---------------------------------------------------------------- launchers
@@ -908,7 +974,8 @@ static hipError_t fwd_d(const void* qkv, int ld, uint32_t bytes, void* o, float*
 
 template <int D>
 static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, const void* dout, uint32_t do_bytes,
-                        const float* lse, float* dvec, void* dqkv, float* scratch, int B, int S, int nh, int nkv, hipStream_t st) {
+                        const float* lse, float* dvec, void* dqkv, float* scratch, int B, int S, int nh, int nkv,
+                        const float* rope, int rope_seq, hipStream_t st) {
     constexpr int LDS_KV = 8 * Tile<D>::BYTES + 1024;
     hipError_t e = set_lds(k_attn_bwd_dkv<D>, LDS_KV);
     if (e != hipSuccess) return e;
@@ -922,19 +989,20 @@ static hipError_t bwd_d(const void* qkv, int ld, uint32_t bytes, const void* o, 
         const long rows = (long)B * S * nh;
         k_attn_delta<D><<<(unsigned)((2 * rows + 255) / 256), 256, 0, st>>>((const bf16_t*)o, (const bf16_t*)dout, dvec, S, nh, rows);
         k_attn_bwd_both<D><<<grid + grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                                      (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch);
+                                                                      (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch, rope, rope_seq);
     } else {
         constexpr int LDS = 4 * Tile<D>::BYTES;
         e = set_lds(k_attn_bwd_dq<D, 1>, LDS);
         if (e != hipSuccess) return e;
         k_attn_bwd_dq<D, 1><<<grid, ATHREADS, LDS, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)o, (const bf16_t*)dout, do_bytes, lse, dvec,
-                                                         (bf16_t*)dqkv, S, nh, nkv, B);
+                                                         (bf16_t*)dqkv, S, nh, nkv, B, rope, rope_seq);
         k_attn_bwd_dkv<D><<<grid_kv, KVTHREADS, LDS_KV, st>>>((const bf16_t*)qkv, ld, bytes, (const bf16_t*)dout, do_bytes, lse,
-                                                              dvec, (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch);
+                                                              dvec, (bf16_t*)dqkv, S, nh, nkv, B, hs, scratch, rope, rope_seq);
     }
     if (hs > 1) {
-        const long n = (long)B * S * (nkv * D / 4);
-        k_attn_dkv_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(scratch, hs, (long)B * S, nkv * D, (bf16_t*)dqkv, ld, nh * D);
+        const long n = (long)B * S * (nkv * D / 8);
+        k_attn_dkv_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(scratch, hs, (long)B * S, nkv * D, D, S, (bf16_t*)dqkv, ld, nh * D,
+                                                                       rope, rope_seq);
     }
     return hipGetLastError();
 }
@@ -948,12 +1016,14 @@ hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, in
 }
 
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                         void* dqkv, float* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st) {
+                         void* dqkv, float* scratch, int B, int S, int nh, int nkv, int d,
+                         const float* rope, int rope_seq, hipStream_t st) {
     const long bytes = (long)B * S * ld * 2;
     const long do_bytes = (long)B * S * nh * d * 2;
     if (bytes >= (1L << 32) - (1L << 25)) return hipErrorInvalidValue;
-    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, scratch, B, S, nh, nkv, st);
-    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, scratch, B, S, nh, nkv, st);
+    if (rope && rope_seq < S) return hipErrorInvalidValue;
+    if (d == 128) return bwd_d<128>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, scratch, B, S, nh, nkv, rope, rope_seq, st);
+    if (d == 64) return bwd_d<64>(qkv, ld, (uint32_t)bytes, o, dout, (uint32_t)do_bytes, lse, dvec, dqkv, scratch, B, S, nh, nkv, rope, rope_seq, st);
     return hipErrorInvalidValue;
 }
 

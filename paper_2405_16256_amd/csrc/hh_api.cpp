@@ -20,7 +20,8 @@ hipError_t gemm_bf16(const GemmDesc& g, hipStream_t st);
 hipError_t gemm_f32(const GemmDesc& g, hipStream_t st);
 hipError_t attn_bf16_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st);
 hipError_t attn_bf16_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                         void* dqkv, float* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st);
+                         void* dqkv, float* scratch, int B, int S, int nh, int nkv, int d,
+                         const float* rope, int rope_seq, hipStream_t st);
 size_t attn_bf16_bwd_scratch_bytes(int B, int S, int nh, int nkv, int d);
 hipError_t attn_f32_fwd(const void* qkv, int ld, void* o, float* lse, int B, int S, int nh, int nkv, int d, hipStream_t st);
 hipError_t attn_f32_bwd(const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
@@ -36,9 +37,13 @@ size_t attn_bwd_scratch_bytes(int dtype, int B, int S, int nh, int nkv, int d) {
     return dtype == DT_BF16 ? attn_bf16_bwd_scratch_bytes(B, S, nh, nkv, d) : 0;
 }
 hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const void* dout, const float* lse, float* dvec,
-                    void* dqkv, void* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st) {
-    return dtype == DT_BF16 ? attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, (float*)scratch, B, S, nh, nkv, d, st)
-                            : attn_f32_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, nkv, d, st);
+                    void* dqkv, void* scratch, int B, int S, int nh, int nkv, int d,
+                    const float* rope_table, int rope_seq, hipStream_t st) {
+    // bf16: the kernels take the rotary embedding back out of dq and dk as they write them; fp32: a pass of its own
+    if (dtype == DT_BF16) return attn_bf16_bwd(qkv, ld, o, dout, lse, dvec, dqkv, (float*)scratch, B, S, nh, nkv, d, rope_table, rope_seq, st);
+    const hipError_t e = attn_f32_bwd(qkv, ld, o, dout, lse, dvec, dqkv, B, S, nh, nkv, d, st);
+    if (e != hipSuccess || !rope_table) return e;
+    return rope(dtype, dqkv, ld, B * S, S, nh + nkv, d, rope_table, rope_seq, 1, st);
 }
 }  // namespace hh
 
@@ -507,8 +512,9 @@ static int layer_bwd_impl(hh_ctx* ctx, const Dims& d, const hh_layer_cfg* cfg, c
     HIP_TRY(tgemm(ctx, dt, desc(GEMM_NN, T, A, H, dh, H, w->wo, A, da, A), st));
     const int Akv = d.Akv, Q3 = d.Q3;
     const int part_w[3] = {A, Akv, Akv}, part_c[3] = {0, A, A + Akv};
-    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, Q3, a, da, lse, dvec, dqkv, at(ws, wl.dkv_part), d.B, d.S, d.nh, d.nkv, d.d, st));
-    TR(HH_TRACE_ELEMENTWISE, 2.0 * T * (A + Akv) * es, rope(dt, dqkv, Q3, T, d.S, d.nh + d.nkv, d.d, ctx->rope_table, ctx->rope_seq, 1, st));
+    // dq | dk | dv of the rotated q, k and of v, with the rotary embedding taken back out of dq and dk
+    TR(HH_TRACE_ATTN_BWD, 2.0 * attn_flop(d), attn_bwd(dt, qkv, Q3, a, da, lse, dvec, dqkv, at(ws, wl.dkv_part), d.B, d.S, d.nh, d.nkv, d.d,
+                                                       ctx->rope_table, ctx->rope_seq, st));
     const bool qkv_packed = (const char*)w->wk == (const char*)w->wq + (size_t)A * H * es &&
                             (const char*)w->wv == (const char*)w->wk + (size_t)Akv * H * es;
     const bool dqkv_packed = (char*)g->wk == (char*)g->wq + (size_t)A * H * 4 && (char*)g->wv == (char*)g->wk + (size_t)Akv * H * 4 &&

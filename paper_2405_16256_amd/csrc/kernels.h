@@ -63,9 +63,12 @@ hipError_t attn_fwd(int dtype, const void* qkv, int ld, void* o, float* lse,
                     int B, int S, int nh, int nkv, int d, hipStream_t st);
 // dqkv [T, ld] receives dq | dk | dv in the same layout.  dvec: scratch [B, nh, S] floats.  scratch: device
 // memory of attn_bwd_scratch_bytes() bytes (partial dK, dV sums when the query heads that share a key/value head
-// are spread over several workgroups; may be null when that size is 0).
+// are spread over several workgroups; may be null when that size is 0).  rope_table (as for rope(), rope_seq >= S;
+// null: none): q and k were rotated before the forward call, and dq, dk are written as gradients of the
+// unrotated q, k (the backward rotation applied before the one rounding to the storage type).
 size_t attn_bwd_scratch_bytes(int dtype, int B, int S, int nh, int nkv, int d);
 hipError_t attn_bwd(int dtype, const void* qkv, int ld, const void* o, const void* dout, const float* lse,
-                    float* dvec, void* dqkv, void* scratch, int B, int S, int nh, int nkv, int d, hipStream_t st);
+                    float* dvec, void* dqkv, void* scratch, int B, int S, int nh, int nkv, int d,
+                    const float* rope_table, int rope_seq, hipStream_t st);
 
 }  // namespace hh
