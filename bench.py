@@ -137,7 +137,7 @@ def main():
         del src, dst
     # Warm-up steps run with every kernel family bracketed by events: this gives the per-family breakdown and
     # names the dominant GEMM family.  In the timed region only that family is bracketed, because each event
-    # between two kernels costs a few microseconds (33 launches per layer pass).
+    # between two kernels costs a few microseconds (28 launches per layer pass).
     fam_all = {}
     traced_warm = a.warmup - 1 if not a.no_trace else 0     # the very first step pays one-time costs: not traced
     for i in range(a.warmup):
