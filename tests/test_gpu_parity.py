@@ -618,10 +618,13 @@ def test_bf16_grouped_queries_summed_inside_one_workgroup(ctx):
     check_layer(ctx, I.LayerShape(256, 16, 64, 512, 2048, 8, n_kv_heads=8), True, 78, label="gqa-heads-in-one-workgroup")
 
 
-def test_stage_step_recorded_in_a_graph_replays_bit_identically(ctx):
+@pytest.mark.parametrize("seq", [300, 1100])
+def test_stage_step_recorded_in_a_graph_replays_bit_identically(ctx, seq):
     # callers may record the stage step into a HIP graph (no allocation, host synchronisation or memset happens inside once
-    # the context is warm); every replay, with eager work and synchronisations in between, must give the eager result bit for bit
-    s, k, M = I.LayerShape(512, 8, 64, 768, 300, 2, n_kv_heads=2), 2, 3
+    # the context is warm); every replay, with eager work and synchronisations in between, must give the eager result bit for bit.
+    # seq 1100 takes the attention backward through its joint launch (delta kernel, dQ and dK/dV jobs in one grid, partial
+    # dK/dV sums of the grouped heads summed and rotated by the reduction kernel); seq 300 through the separate kernels.
+    s, k, M = I.LayerShape(512, 8, 64, 768, seq, 2, n_kv_heads=2), 2, 3
     say("[case] graph replay shape=%s k=%d M=%d" % (s, k, M))
     cfg = L.cfg_of(s, True)
     ws_np = [I.layer_weights(91, l, s, True) for l in range(k)]
